@@ -1,0 +1,159 @@
+"""Plain, slow, float64 CPU oracle of the FASA decode step.  TEST INFRASTRUCTURE ONLY.
+
+Every function restates one definition of the paper in numpy float64, with no blocking,
+fusion or reordering beyond what the definition says.  Nothing here is imported by the
+product path; nothing here imports the product path.
+
+Tensor conventions (all "storage" arrays are numpy uint16 holding raw bf16 bits, or
+float32; they are widened exactly to float64 before any arithmetic):
+  q      [Bt][Hq][d]      post-RoPE query of the current step
+  K, V   [Bt][Hkv][>=N][d]  cached post-RoPE keys / values, first N rows valid
+  fc_idx [Hkv][F] int     dominant frequency chunks of each KV head (I_dom, Sec. 4.1)
+FC i is the rotation pair (dim i, dim i + d/2) (rotate-half storage of the FC of
+Sec. 3.1).  GQA: query head hq belongs to KV head hq // G, G = Hq / Hkv; the paper is
+silent on GQA, the reading taken is one score vector and one index set per KV head with
+scores summed over the G query heads of the group.
+
+Pins (tests/test_oracle_*.py): closed-form single-FC RoPE score, hand-worked fixture in
+tests/golden/, F = d/2 equals the full dot product, brute-force top-k, F = d/2 with B = N
+equals dense attention computed by torch's float64 scaled_dot_product_attention, convex
+combination invariants of the attention output.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+# ------------------------------------------------------------------------------------
+# exact widening of storage to float64
+# ------------------------------------------------------------------------------------
+def widen(x: np.ndarray) -> np.ndarray:
+    x = np.asarray(x)
+    if x.dtype == np.uint16:  # raw bf16 bits: the upper half of a float32
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return x.astype(np.float64)
+
+
+# ------------------------------------------------------------------------------------
+# Sec. 3.1: rotary position encoding, FC i rotated by angle m * theta_i
+# ------------------------------------------------------------------------------------
+def rope_reference(x: np.ndarray, m: int, base: float) -> np.ndarray:
+    """Rotate one vector x[d] at position m, one 2x2 rotation matrix per FC (Sec. 3.1, FC
+    definition: R_{m,theta_i} = [[cos, -sin], [sin, cos]], theta_i = base^(-2i/d), i from 0).
+    FC i occupies dims (i, i + d/2).  Written FC by FC on purpose (slow, obvious)."""
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[0]
+    out = np.empty(d, dtype=np.float64)
+    for i in range(d // 2):
+        theta = float(base) ** (-2.0 * i / d)
+        c, s = np.cos(m * theta), np.sin(m * theta)
+        R = np.array([[c, -s], [s, c]])
+        out[[i, i + d // 2]] = R @ x[[i, i + d // 2]]
+    return out
+
+
+# ------------------------------------------------------------------------------------
+# Alg. 2, "Split" + "UpdateCache" of the dominant key parts: the FC-major packed copy
+# ------------------------------------------------------------------------------------
+def pack_kcache(K: np.ndarray, fc_idx: np.ndarray, n_ctx: int) -> np.ndarray:
+    """Kp[b,h,f,n,:] = (K[b,h,n,i_f], K[b,h,n,i_f + d/2]); bit-exact copy, storage dtype kept."""
+    Bt, Hkv, _, d = K.shape
+    F = fc_idx.shape[1]
+    Kp = np.zeros((Bt, Hkv, F, n_ctx, 2), dtype=K.dtype)
+    for h in range(Hkv):
+        for f in range(F):
+            i = int(fc_idx[h, f])
+            Kp[:, h, f, :, 0] = K[:, h, :n_ctx, i]
+            Kp[:, h, f, :, 1] = K[:, h, :n_ctx, i + d // 2]
+    return Kp
+
+
+# ------------------------------------------------------------------------------------
+# Sec. 4.1, TIP: S_t = sum over dominant FCs of the single-FC scores (raw logits)
+# ------------------------------------------------------------------------------------
+def score(q: np.ndarray, K: np.ndarray, fc_idx: np.ndarray, n_ctx: int):
+    """S[b,h,n] = sum_{g<G} sum_{f<F} ( q[b,hG+g,i_f] K[b,h,n,i_f] + q[b,hG+g,i_f+d/2] K[b,h,n,i_f+d/2] ).
+
+    Unscaled, no softmax (Sec. 3.3 calls these "raw score vectors"; Alg. 2 computes
+    q^dom (K^dom)^T).  Also returns D[b,h,n] = the same sum over absolute values of the
+    terms, which scales the forward-error bound of any floating-point evaluation order.
+    """
+    q64 = widen(q)
+    Bt, Hq, d = q64.shape
+    Hkv = K.shape[1]
+    G = Hq // Hkv
+    S = np.zeros((Bt, Hkv, n_ctx))
+    D = np.zeros((Bt, Hkv, n_ctx))
+    for b in range(Bt):
+        for h in range(Hkv):
+            for f in range(fc_idx.shape[1]):
+                i = int(fc_idx[h, f])
+                for dim in (i, i + d // 2):
+                    k_col = widen(K[b, h, :n_ctx, dim])
+                    for g in range(G):
+                        S[b, h] += q64[b, h * G + g, dim] * k_col
+                        D[b, h] += np.abs(q64[b, h * G + g, dim] * k_col)
+    return S, D
+
+
+# ------------------------------------------------------------------------------------
+# Sec. 4.1: T_t = TopK-I(S_t, N_fac)
+# ------------------------------------------------------------------------------------
+def topk_indices(s_row: np.ndarray, budget: int) -> np.ndarray:
+    """Indices of the min(budget, N) largest entries of one score row; equal scores are
+    broken towards the lower index; returned sorted ascending (the set is what matters).
+    The comparison is done on the values as given (float32 rows stay float32)."""
+    n = s_row.shape[0]
+    b = min(int(budget), n)
+    order = np.argsort(-s_row, kind="stable")   # stable: among equals, lower index first
+    return np.sort(order[:b]).astype(np.int64)
+
+
+def topk(S: np.ndarray, budget: int, n_ctx: int) -> np.ndarray:
+    """[Bt][Hkv][min(B,N)] int64."""
+    Bt, Hkv = S.shape[:2]
+    return np.stack([np.stack([topk_indices(S[b, h, :n_ctx], budget) for h in range(Hkv)])
+                     for b in range(Bt)])
+
+
+# ------------------------------------------------------------------------------------
+# Sec. 4.2, FAC: gather the selected rows, exact softmax attention over them
+# ------------------------------------------------------------------------------------
+def sparse_attend(q: np.ndarray, K: np.ndarray, V: np.ndarray, T) -> np.ndarray:
+    """O[b,hq] = softmax_j( q[b,hq] . K[b,h,T_j] / sqrt(d) ) V[b,h,T_j], h = hq // G.
+    T[b][h] is any integer index sequence (order irrelevant).  float64 [Bt][Hq][d]."""
+    q64 = widen(q)
+    Bt, Hq, d = q64.shape
+    Hkv = K.shape[1]
+    G = Hq // Hkv
+    O = np.zeros((Bt, Hq, d))
+    for b in range(Bt):
+        for h in range(Hkv):
+            idx = np.asarray(T[b][h], dtype=np.int64)
+            K_T = widen(K[b, h][idx])           # Gather(K, T)
+            V_T = widen(V[b, h][idx])           # Gather(V, T)
+            for g in range(G):
+                logits = (K_T @ q64[b, h * G + g]) / np.sqrt(d)
+                p = np.exp(logits - logits.max())
+                p /= p.sum()
+                O[b, h * G + g] = p @ V_T
+    return O
+
+
+def dense_attend(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_ctx: int) -> np.ndarray:
+    """Full-KV decode attention: FAC with T = all N tokens (the paper's FKV baseline)."""
+    Bt, Hkv = K.shape[:2]
+    T = [[np.arange(n_ctx) for _ in range(Hkv)] for _ in range(Bt)]
+    return sparse_attend(q, K, V, T)
+
+
+# ------------------------------------------------------------------------------------
+# the whole decode step: TIP -> TopK-I -> FAC
+# ------------------------------------------------------------------------------------
+def decode_step(q, K, V, fc_idx, n_ctx: int, budget: int, score_dtype=np.float32):
+    """Returns (S float64, D, T, O).  The ranking is taken on S rounded to `score_dtype`
+    (the precision the method's score vector is held in on the device: float32)."""
+    S, D = score(q, K, fc_idx, n_ctx)
+    T = topk(S.astype(score_dtype), budget, n_ctx)
+    O = sparse_attend(q, K, V, T)
+    return S, D, T, O
