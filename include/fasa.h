@@ -1,0 +1,146 @@
+/*
+ * fasa.h -- C ABI of the MI355X (gfx950) FASA decode hot path.
+ *
+ * FASA = frequency-aware sparse attention.  One decode step of one attention layer does
+ *   (1) TIP   : score every cached token with a partial dot product over the KV head's
+ *               dominant RoPE frequency chunks (FCs)                     (paper Sec. 4.1)
+ *   (2) TopK-I: keep the indices of the B best-scored tokens per KV head (paper Sec. 4.1)
+ *   (3) FAC   : exact softmax attention over the gathered B rows of K, V (paper Sec. 4.2)
+ * The dominant-FC list I_dom is an input (it comes from an offline calibration, Alg. 1).
+ *
+ * Conventions that hold for every entry point
+ *   - All tensor pointers are DEVICE pointers (HBM) unless the name ends in _host.  The caller owns
+ *     every buffer, including the workspace; the library allocates and frees nothing on the device.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream).  No entry
+ *     point synchronises the host.  Calls that share a workspace must be ordered by the stream.
+ *   - Return value: FASA_OK (0) or a negative fasa_status.  Arguments are validated before the
+ *     first HIP call, so error paths work on a host without a GPU.  Inputs must be finite; the
+ *     ranking of NaN scores is unspecified.
+ *   - FC i of a d-dim head vector is the rotation pair (dim i, dim i + d/2) ("rotate-half"
+ *     storage of the FC of paper Sec. 3.1); FCs are never split (paper App. D.2).
+ *   - GQA: query head hq reads KV head hq / G, G = n_q_heads / n_kv_heads.  There is one score
+ *     vector and one index set per KV head; scores are summed over the G query heads of the group.
+ *   - Layouts (row-major, innermost last):
+ *       q      [batch][n_q_heads][head_dim]                 dtype
+ *       K, V   [batch][n_kv_heads][>= n_ctx tokens][head_dim] dtype, element strides kv_stride_{b,h,n},
+ *                                                            K holds post-RoPE keys
+ *       fc_idx [n_kv_heads][n_fc]                           int32, distinct values in [0, head_dim/2)
+ *       Kp     [batch][n_kv_heads][n_fc][n_cap][2]          dtype, FC-major copy of the dominant K dims
+ *       S      [batch][n_kv_heads][n_cap]                   float32, entries >= n_ctx untouched
+ *       T      [batch][n_kv_heads][min(budget, n_ctx)]      int32, a SET: order unspecified, no duplicates
+ *       O      [batch][n_q_heads][head_dim]                 float32
+ *   - Alignment: every pointer 16-byte aligned; n_cap a multiple of 64; kv_stride_n a multiple of 8
+ *     elements and >= head_dim; head_dim == 128; 1 <= G <= 8.
+ */
+#ifndef FASA_H
+#define FASA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FASA_OK = 0,
+  FASA_EINVAL = -1,       /* null pointer, bad shape, misaligned pointer, bad fc_idx */
+  FASA_EUNSUPPORTED = -2, /* valid request outside what the kernels are built for      */
+  FASA_EWORKSPACE = -3,   /* workspace smaller than fasa_workspace_bytes()             */
+  FASA_EHIP = -4          /* a HIP call failed; see fasa_last_hip_error()              */
+} fasa_status;
+
+typedef enum { FASA_BF16 = 0, FASA_F32 = 1 } fasa_dtype;
+
+typedef struct fasa_shape {
+  int32_t batch;       /* Bt                                                            */
+  int32_t n_q_heads;   /* Hq                                                            */
+  int32_t n_kv_heads;  /* Hkv, divides Hq                                               */
+  int32_t head_dim;    /* d                                                             */
+  int32_t n_fc;        /* F = |I_dom| per KV head (paper: N_tip), 1 .. d/2              */
+  int32_t n_ctx;       /* N: valid cached tokens this step (paper: t), 1 .. n_cap       */
+  int32_t n_cap;       /* token capacity of the Kp and S planes                         */
+  int32_t budget;      /* B (paper: N_fac) >= 1; B >= N selects every token             */
+  int32_t dtype;       /* fasa_dtype of q, K, V, Kp                                     */
+  int32_t reserved;    /* must be 0                                                     */
+  int64_t kv_stride_b; /* element strides of K and V; the head_dim stride is 1          */
+  int64_t kv_stride_h;
+  int64_t kv_stride_n;
+} fasa_shape;
+
+/* Bytes of device workspace that any entry point below needs for `shape` (host-only, pure).
+ * Returns 0 if the shape is invalid. */
+size_t fasa_workspace_bytes(const fasa_shape* shape);
+
+/* Host-side check of a dominant-FC list (HOST pointer [n_kv_heads][n_fc]): every value in
+ * [0, head_dim/2), no duplicates within a head (an FC is selected whole or not at all,
+ * paper App. D.2). */
+int fasa_validate_fc_idx(const fasa_shape* shape, const int32_t* fc_idx_host);
+
+/* Dominant-key cache maintenance (paper Alg. 2: Split + UpdateCache of k^dom).
+ * For tokens n in [n_begin, n_end), 0 <= n_begin <= n_end <= n_cap:
+ *     Kp[b,h,f,n,0] = K[b,h,n,i],  Kp[b,h,f,n,1] = K[b,h,n,i + d/2],  i = fc_idx[h,f]
+ * A bit-exact copy.  Full pack after prefill: [0, N); append of one decoded token: [N-1, N).
+ * shape->n_ctx and shape->budget are not used. */
+int fasa_pack_kcache(const fasa_shape* shape, const void* K, const int32_t* fc_idx, void* Kp,
+                     int32_t n_begin, int32_t n_end, void* stream);
+
+/* TIP scoring (paper Sec. 4.1, S_t = sum over I_dom of single-FC scores; Alg. 2: q^dom (K^dom)^T):
+ *     S[b,h,n] = sum_{g<G} sum_{f<F} ( q[b,hG+g,i_f] Kp[b,h,f,n,0] + q[b,hG+g,i_f+d/2] Kp[b,h,f,n,1] )
+ * for n < n_ctx.  Raw logits: no 1/sqrt(d), no softmax.  float32 accumulation. */
+int fasa_score(const fasa_shape* shape, const void* q, const void* Kp, const int32_t* fc_idx,
+               float* S, void* stream);
+
+/* TopK-I (paper Sec. 4.1, T_t = TopK-I(S_t, N_fac)): for each (b,h) the index set of the
+ * min(budget, n_ctx) largest S[b,h,0:n_ctx].  Equal scores are resolved towards the lower index;
+ * -0 and +0 are equal.  Uses and overwrites the workspace. */
+int fasa_topk(const fasa_shape* shape, const float* S, int32_t* T, void* ws, size_t ws_bytes,
+              void* stream);
+
+/* FAC (paper Sec. 4.2, eq. fac_output): for every query head hq, h = hq / G,
+ *     O[b,hq] = softmax_j( q[b,hq] . K[b,h,T[b,h,j]] / sqrt(d) ) V[b,h,T[b,h,j]]
+ * over the min(budget, n_ctx) entries of T[b,h].  Rows are used as cached (no re-rotation).
+ * float32 accumulation and output.  T entries must lie in [0, n_ctx); entries outside are clamped
+ * into that range before use (memory safety only: the result is then unspecified). */
+int fasa_sparse_attend(const fasa_shape* shape, const void* q, const void* K, const void* V,
+                       const int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream);
+
+/* Full-KV decode attention over tokens [0, n_ctx) (the paper's FKV baseline, Sec. 4.4); same
+ * kernel family as fasa_sparse_attend with contiguous loads.  budget and n_fc are not used. */
+int fasa_dense_attend(const fasa_shape* shape, const void* q, const void* K, const void* V,
+                      float* O, void* ws, size_t ws_bytes, void* stream);
+
+/* One whole decode step on one stream without host round trips (paper Sec. 4.1-4.2; Alg. 2 order:
+ * the new key joins the dominant cache before scoring):
+ *   if k_new != NULL: K[b,h,n_ctx-1,:] = k_new[b,h,:], V[b,h,n_ctx-1,:] = v_new[b,h,:]
+ *                     ([batch][n_kv_heads][head_dim], dtype) and the row's dominant FCs go to Kp;
+ *                     k_new and v_new must be both NULL or both non-NULL;
+ *   then fasa_score -> S, fasa_topk -> T, fasa_sparse_attend -> O.
+ * S and T are outputs the caller may inspect (S doubles as the score scratch). */
+int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,
+                     const int32_t* fc_idx, const void* k_new, const void* v_new, float* S,
+                     int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream);
+
+/* Static description of a status code. */
+const char* fasa_strerror(int status);
+/* hipError_t value of the last failed HIP call on this thread (0 if none). */
+int fasa_last_hip_error(void);
+/* Library version, major * 1000 + minor. */
+int fasa_version(void);
+
+/* Per-kernel timing for benchmarks.  While enabled, every kernel launch records the GPU
+ * timestamps of its own start and end (kernel execution only, no launch gap).
+ * fasa_profile_collect() synchronises the device, folds the recorded launches into per-kernel
+ * totals and returns the number of distinct kernels seen since the last reset;
+ * fasa_profile_entry() reads entry i: kernel name (copied, NUL-terminated), launches, total ms.
+ * Not thread-safe; meant for a single benchmarking thread. */
+int fasa_profile_enable(int on);
+int fasa_profile_reset(void);
+int fasa_profile_collect(void);
+int fasa_profile_entry(int i, char* name_out, size_t name_cap, int64_t* launches_out,
+                       double* total_ms_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASA_H */

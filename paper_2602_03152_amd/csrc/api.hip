@@ -1,0 +1,288 @@
+// C-ABI entry points: argument validation (no HIP call before it passes), workspace carve-up,
+// stage sequencing on the caller's stream, per-kernel profiler.
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "fasa_internal.h"
+
+namespace fasa {
+
+// ---------------------------------------------------------------------------------------------
+// last HIP error (per thread)
+// ---------------------------------------------------------------------------------------------
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+// ---------------------------------------------------------------------------------------------
+// profiler
+// ---------------------------------------------------------------------------------------------
+struct ProfRec { const char* name; hipEvent_t a, b; };
+struct ProfSum { std::string name; int64_t launches; double ms; };
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof_recs;
+static std::vector<ProfSum> g_prof_sums;
+
+bool profile_on() { return g_prof_on; }
+
+hipError_t profile_events(const char* name, hipEvent_t* start, hipEvent_t* stop) {
+  hipError_t e = hipEventCreate(start);
+  if (e != hipSuccess) return e;
+  e = hipEventCreate(stop);
+  if (e != hipSuccess) { (void)hipEventDestroy(*start); return e; }
+  g_prof_recs.push_back({name, *start, *stop});
+  return hipSuccess;
+}
+
+static int profile_fold() {
+  hipError_t e = hipDeviceSynchronize();
+  if (e != hipSuccess) { set_last_hip_error(e); return FASA_EHIP; }
+  for (auto& r : g_prof_recs) {
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, r.a, r.b);
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+    if (e != hipSuccess) { set_last_hip_error(e); continue; }
+    bool found = false;
+    for (auto& s : g_prof_sums)
+      if (s.name == r.name) { s.launches++; s.ms += ms; found = true; break; }
+    if (!found) g_prof_sums.push_back({r.name, 1, (double)ms});
+  }
+  g_prof_recs.clear();
+  return (int)g_prof_sums.size();
+}
+
+// ---------------------------------------------------------------------------------------------
+// plans and workspace
+// ---------------------------------------------------------------------------------------------
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+AttendPlan plan_attend(int rows, int count) {
+  // aim at ~1024 workgroups over the chip, at least one 64-token batch round per workgroup
+  const long long total = (long long)rows * count;
+  long long tps = (total + 1023) / 1024;
+  tps = ((tps + 63) / 64) * 64;
+  if (tps < 64) tps = 64;
+  AttendPlan p;
+  p.count = count;
+  p.tok_per_split = (int)tps;
+  p.n_splits = (int)((count + tps - 1) / tps);
+  return p;
+}
+
+WsLayout ws_layout(const fasa_shape& s) {
+  WsLayout w{};
+  w.rows = s.batch * s.n_kv_heads;
+  const int G = s.n_q_heads / s.n_kv_heads;
+  const int bsel = s.budget < s.n_ctx ? s.budget : s.n_ctx;
+  const int sp_sparse = plan_attend(w.rows, bsel).n_splits;
+  const int sp_dense = plan_attend(w.rows, s.n_ctx).n_splits;
+  w.max_splits = sp_sparse > sp_dense ? sp_sparse : sp_dense;
+  size_t off = 0;
+  w.hist_off = off;      off = align256(off + (size_t)w.rows * kHistBins * sizeof(uint32_t));
+  w.ctl_off = off;       off = align256(off + (size_t)w.rows * sizeof(RowCtl));
+  w.cand_off = off;      off = align256(off + (size_t)w.rows * s.n_cap * sizeof(uint2));
+  w.part_acc_off = off;  off = align256(off + (size_t)w.rows * w.max_splits * G * kHeadDim * sizeof(float));
+  w.part_ml_off = off;   off = align256(off + (size_t)w.rows * w.max_splits * G * 2 * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+// ---------------------------------------------------------------------------------------------
+// validation
+// ---------------------------------------------------------------------------------------------
+static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+enum Need : unsigned { kNeedNone = 0, kNeedCtx = 1, kNeedBudget = 2, kNeedFc = 4, kNeedStrides = 8 };
+
+static int check_shape(const fasa_shape* s, unsigned need) {
+  if (!s) return FASA_EINVAL;
+  if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->head_dim < 2) return FASA_EINVAL;
+  if (s->head_dim % 2 != 0 || s->n_q_heads % s->n_kv_heads != 0) return FASA_EINVAL;
+  if (s->reserved != 0) return FASA_EINVAL;
+  if (s->dtype != FASA_BF16 && s->dtype != FASA_F32) return FASA_EINVAL;
+  if (s->n_cap < 1 || s->n_cap % 64 != 0) return FASA_EINVAL;
+  if ((long long)s->batch * s->n_kv_heads > 65535) return FASA_EUNSUPPORTED;
+  if (need & kNeedCtx) { if (s->n_ctx < 1 || s->n_ctx > s->n_cap) return FASA_EINVAL; }
+  if (need & kNeedBudget) { if (s->budget < 1) return FASA_EINVAL; }
+  if (need & kNeedFc) { if (s->n_fc < 1 || s->n_fc > s->head_dim / 2) return FASA_EINVAL; }
+  if (need & kNeedStrides) {
+    if (s->kv_stride_n < s->head_dim || s->kv_stride_n % 8 != 0) return FASA_EINVAL;
+    if (s->kv_stride_h < 0 || s->kv_stride_b < 0 || s->kv_stride_h % 8 != 0 || s->kv_stride_b % 8 != 0)
+      return FASA_EINVAL;
+  }
+  if (s->head_dim != kHeadDim) return FASA_EUNSUPPORTED;
+  if (s->n_q_heads / s->n_kv_heads > kMaxGroup) return FASA_EUNSUPPORTED;
+  return FASA_OK;
+}
+
+static int check_ws(const fasa_shape* s, const void* ws, size_t ws_bytes) {
+  if (!ws || !aligned16(ws)) return FASA_EINVAL;
+  if (ws_bytes < ws_layout(*s).total) return FASA_EWORKSPACE;
+  return FASA_OK;
+}
+
+#define FASA_HIP(expr) do { if ((expr) != hipSuccess) return FASA_EHIP; } while (0)
+
+}  // namespace fasa
+
+using namespace fasa;
+
+extern "C" {
+
+size_t fasa_workspace_bytes(const fasa_shape* shape) {
+  if (check_shape(shape, kNeedCtx | kNeedBudget) != FASA_OK) return 0;
+  return ws_layout(*shape).total;
+}
+
+int fasa_validate_fc_idx(const fasa_shape* shape, const int32_t* fc_idx_host) {
+  int rc = check_shape(shape, kNeedFc);
+  if (rc != FASA_OK) return rc;
+  if (!fc_idx_host) return FASA_EINVAL;
+  const int half = shape->head_dim / 2;
+  for (int h = 0; h < shape->n_kv_heads; ++h) {
+    bool seen[4096] = {false};
+    if (half > 4096) return FASA_EUNSUPPORTED;
+    for (int f = 0; f < shape->n_fc; ++f) {
+      const int i = fc_idx_host[h * shape->n_fc + f];
+      if (i < 0 || i >= half || seen[i]) return FASA_EINVAL;
+      seen[i] = true;
+    }
+  }
+  return FASA_OK;
+}
+
+int fasa_pack_kcache(const fasa_shape* shape, const void* K, const int32_t* fc_idx, void* Kp,
+                     int32_t n_begin, int32_t n_end, void* stream) {
+  int rc = check_shape(shape, kNeedFc | kNeedStrides);
+  if (rc != FASA_OK) return rc;
+  if (!K || !fc_idx || !Kp || !aligned16(K) || !aligned16(Kp) || !aligned16(fc_idx)) return FASA_EINVAL;
+  if (n_begin < 0 || n_end < n_begin || n_end > shape->n_cap) return FASA_EINVAL;
+  if (n_begin == n_end) return FASA_OK;
+  FASA_HIP(launch_pack(*shape, K, fc_idx, Kp, n_begin, n_end, (hipStream_t)stream));
+  return FASA_OK;
+}
+
+int fasa_score(const fasa_shape* shape, const void* q, const void* Kp, const int32_t* fc_idx,
+               float* S, void* stream) {
+  int rc = check_shape(shape, kNeedCtx | kNeedFc);
+  if (rc != FASA_OK) return rc;
+  if (!q || !Kp || !fc_idx || !S) return FASA_EINVAL;
+  if (!aligned16(q) || !aligned16(Kp) || !aligned16(fc_idx) || !aligned16(S)) return FASA_EINVAL;
+  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, nullptr, (hipStream_t)stream));
+  return FASA_OK;
+}
+
+int fasa_topk(const fasa_shape* shape, const float* S, int32_t* T, void* ws, size_t ws_bytes,
+              void* stream) {
+  int rc = check_shape(shape, kNeedCtx | kNeedBudget);
+  if (rc != FASA_OK) return rc;
+  if (!S || !T || !aligned16(S) || !aligned16(T)) return FASA_EINVAL;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc != FASA_OK) return rc;
+  const WsLayout w = ws_layout(*shape);
+  char* base = (char*)ws;
+  uint32_t* hist = (uint32_t*)(base + w.hist_off);
+  RowCtl* ctl = (RowCtl*)(base + w.ctl_off);
+  uint2* cand = (uint2*)(base + w.cand_off);
+  hipStream_t st = (hipStream_t)stream;
+  FASA_HIP(launch_prologue(*shape, hist, ctl, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, st));
+  if (shape->budget < shape->n_ctx) FASA_HIP(launch_hist(*shape, S, hist, st));
+  FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st));
+  return FASA_OK;
+}
+
+static int attend_common(const fasa_shape* shape, bool dense, const void* q, const void* K,
+                         const void* V, const int32_t* T, float* O, void* ws, size_t ws_bytes,
+                         void* stream) {
+  int rc = check_shape(shape, kNeedCtx | kNeedStrides | (dense ? 0u : (unsigned)kNeedBudget));
+  if (rc != FASA_OK) return rc;
+  if (!q || !K || !V || !O || (!dense && !T)) return FASA_EINVAL;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || (!dense && !aligned16(T)))
+    return FASA_EINVAL;
+  fasa_shape s = *shape;
+  if (dense) s.budget = s.n_ctx;
+  rc = check_ws(&s, ws, ws_bytes);
+  if (rc != FASA_OK) return rc;
+  const WsLayout w = ws_layout(s);
+  char* base = (char*)ws;
+  FASA_HIP(launch_attend(s, dense, q, K, V, T, O, (float*)(base + w.part_acc_off),
+                         (float*)(base + w.part_ml_off), (hipStream_t)stream));
+  return FASA_OK;
+}
+
+int fasa_sparse_attend(const fasa_shape* shape, const void* q, const void* K, const void* V,
+                       const int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream) {
+  return attend_common(shape, false, q, K, V, T, O, ws, ws_bytes, stream);
+}
+
+int fasa_dense_attend(const fasa_shape* shape, const void* q, const void* K, const void* V,
+                      float* O, void* ws, size_t ws_bytes, void* stream) {
+  return attend_common(shape, true, q, K, V, nullptr, O, ws, ws_bytes, stream);
+}
+
+int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,
+                     const int32_t* fc_idx, const void* k_new, const void* v_new, float* S,
+                     int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(shape, kNeedCtx | kNeedBudget | kNeedFc | kNeedStrides);
+  if (rc != FASA_OK) return rc;
+  if (!q || !K || !V || !Kp || !fc_idx || !S || !T || !O) return FASA_EINVAL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return FASA_EINVAL;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(Kp) || !aligned16(fc_idx) ||
+      !aligned16(S) || !aligned16(T) || !aligned16(O) || !aligned16(k_new) || !aligned16(v_new))
+    return FASA_EINVAL;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc != FASA_OK) return rc;
+  const WsLayout w = ws_layout(*shape);
+  char* base = (char*)ws;
+  uint32_t* hist = (uint32_t*)(base + w.hist_off);
+  RowCtl* ctl = (RowCtl*)(base + w.ctl_off);
+  uint2* cand = (uint2*)(base + w.cand_off);
+  hipStream_t st = (hipStream_t)stream;
+  const bool select_all = shape->budget >= shape->n_ctx;
+  FASA_HIP(launch_prologue(*shape, hist, ctl, K, V, Kp, fc_idx, k_new, v_new, st));
+  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, select_all ? nullptr : hist, st));
+  FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st));
+  FASA_HIP(launch_attend(*shape, false, q, K, V, T, O, (float*)(base + w.part_acc_off),
+                         (float*)(base + w.part_ml_off), st));
+  return FASA_OK;
+}
+
+const char* fasa_strerror(int status) {
+  switch (status) {
+    case FASA_OK: return "ok";
+    case FASA_EINVAL: return "invalid argument (null or misaligned pointer, bad shape or index list)";
+    case FASA_EUNSUPPORTED: return "shape outside what the kernels support (head_dim must be 128, GQA group <= 8)";
+    case FASA_EWORKSPACE: return "workspace smaller than fasa_workspace_bytes()";
+    case FASA_EHIP: return "HIP call failed (see fasa_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+int fasa_last_hip_error(void) { return g_last_hip_error; }
+int fasa_version(void) { return 1000; }
+
+int fasa_profile_enable(int on) { g_prof_on = on != 0; return FASA_OK; }
+
+int fasa_profile_reset(void) {
+  for (auto& r : g_prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  g_prof_recs.clear();
+  g_prof_sums.clear();
+  return FASA_OK;
+}
+
+int fasa_profile_collect(void) { return profile_fold(); }
+
+int fasa_profile_entry(int i, char* name_out, size_t name_cap, int64_t* launches_out,
+                       double* total_ms_out) {
+  if (i < 0 || i >= (int)g_prof_sums.size() || !name_out || name_cap == 0) return FASA_EINVAL;
+  const ProfSum& s = g_prof_sums[i];
+  std::strncpy(name_out, s.name.c_str(), name_cap - 1);
+  name_out[name_cap - 1] = '\0';
+  if (launches_out) *launches_out = s.launches;
+  if (total_ms_out) *total_ms_out = s.ms;
+  return FASA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,96 @@
+// Internal declarations shared by the translation units of libfasa (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <tuple>
+#include <utility>
+
+#include "fasa.h"
+
+namespace fasa {
+
+// ---------------------------------------------------------------------------------------------
+// constants of the selection stage
+// ---------------------------------------------------------------------------------------------
+constexpr int kHistBits = 12;              // coarse bins = top 12 bits of the order-preserving key
+constexpr int kHistBins = 1 << kHistBits;  // (sign, 8 exponent bits, 3 mantissa bits)
+constexpr int kKeyLowBits = 32 - kHistBits;
+constexpr int kHeadDim = 128;
+constexpr int kMaxGroup = 8;
+
+// per-(b,h) row counters of the selection stage
+struct RowCtl {
+  uint32_t n_sel;   // winners written so far (tokens in bins above the threshold bin)
+  uint32_t n_cand;  // candidates collected from the threshold bin
+  uint32_t done;    // blocks of this row that finished their slice
+  uint32_t pad;
+};
+
+// Workspace carve-up (all offsets 256-byte aligned).
+struct WsLayout {
+  size_t hist_off, ctl_off, cand_off, part_acc_off, part_ml_off, total;
+  int rows, max_splits;
+};
+
+struct AttendPlan {
+  int count;          // tokens attended per row
+  int tok_per_split;  // multiple of 64
+  int n_splits;
+};
+
+AttendPlan plan_attend(int rows, int count);
+WsLayout ws_layout(const fasa_shape& s);
+
+// ---------------------------------------------------------------------------------------------
+// launch helper: plain launch, or a launch bracketed by its own start/stop timestamps
+// ---------------------------------------------------------------------------------------------
+bool profile_on();
+// Hands out a fresh event pair owned by the profiler and remembers it under `name`.
+hipError_t profile_events(const char* name, hipEvent_t* start, hipEvent_t* stop);
+void set_last_hip_error(hipError_t e);
+
+template <typename... KArgs, typename... Args>
+inline hipError_t launch(const char* name, void (*kernel)(KArgs...), dim3 grid, dim3 block,
+                         hipStream_t stream, Args&&... args) {
+  static_assert(sizeof...(KArgs) == sizeof...(Args), "kernel argument count");
+  std::tuple<KArgs...> vals{static_cast<KArgs>(std::forward<Args>(args))...};
+  void* ptrs[sizeof...(KArgs) ? sizeof...(KArgs) : 1];
+  std::apply([&](auto&... v) { size_t i = 0; ((ptrs[i++] = (void*)&v), ...); }, vals);
+  hipError_t e;
+  if (profile_on()) {
+    hipEvent_t a = nullptr, b = nullptr;
+    e = profile_events(name, &a, &b);
+    if (e == hipSuccess)
+      e = hipExtLaunchKernel((const void*)kernel, grid, block, ptrs, 0, stream, a, b, 0);
+  } else {
+    e = hipLaunchKernel((const void*)kernel, grid, block, ptrs, 0, stream);
+  }
+  if (e != hipSuccess) set_last_hip_error(e);
+  return e;
+}
+
+// ---------------------------------------------------------------------------------------------
+// stage launchers (defined in pack.hip / score.hip / topk.hip / attend.hip); shapes are already
+// validated when these are called
+// ---------------------------------------------------------------------------------------------
+hipError_t launch_pack(const fasa_shape& s, const void* K, const int32_t* fc_idx, void* Kp,
+                       int n_begin, int n_end, hipStream_t st);
+// hist == nullptr: scores only
+hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
+                        float* S, uint32_t* hist, hipStream_t st);
+// clears histogram + row counters; with k_new also appends the new K/V row and its packed FCs
+hipError_t launch_prologue(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, void* K, void* V,
+                           void* Kp, const int32_t* fc_idx, const void* k_new, const void* v_new,
+                           hipStream_t st);
+hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st);
+hipError_t launch_select(const fasa_shape& s, const float* S, const uint32_t* hist, RowCtl* ctl,
+                         uint2* cand, int32_t* T, hipStream_t st);
+hipError_t launch_attend(const fasa_shape& s, bool dense, const void* q, const void* K,
+                         const void* V, const int32_t* T, float* O, float* part_acc, float* part_ml,
+                         hipStream_t st);
+
+}  // namespace fasa

@@ -1,0 +1,121 @@
+// Dominant-key cache maintenance: the FC-major packed copy Kp of the dominant K dims
+// (paper Alg. 2, Split + UpdateCache of k^dom), and the per-step prologue that clears the
+// selection counters and appends a freshly decoded K/V row.
+#include "fasa_device.h"
+#include "fasa_internal.h"
+
+namespace fasa {
+
+constexpr int kPackTile = 64;  // tokens per workgroup
+
+// One workgroup copies the dominant columns of kPackTile cached key rows.
+// Rows are read whole and coalesced into LDS (the dominant dims are scattered over the row, so
+// every 128-byte line of the row is touched anyway); the F planes are then written with one
+// (lo, hi) pair per token, contiguous along the token axis.
+template <typename ET>
+__global__ __launch_bounds__(256) void pack_kernel(const ET* __restrict__ K,
+                                                   const int32_t* __restrict__ fc_idx,
+                                                   ET* __restrict__ Kp, int Hkv, int F, int n_cap,
+                                                   int n_begin, int n_end, long long sb,
+                                                   long long sh, long long sn) {
+  constexpr int D = kHeadDim;
+  constexpr int PITCH = D + 16 / sizeof(ET);  // keeps 16-byte alignment, staggers LDS banks
+  __shared__ __align__(16) ET tile[kPackTile][PITCH];
+  __shared__ int fcs[D / 2];
+
+  const int row = blockIdx.y;
+  const int b = row / Hkv, h = row % Hkv;
+  const int n0 = n_begin + blockIdx.x * kPackTile;
+  const int nt = min(kPackTile, n_end - n0);
+  const int t = threadIdx.x;
+
+  if (t < F) fcs[t] = fc_idx[h * F + t];
+
+  constexpr int VEC = 16 / sizeof(ET);    // elements per 16-byte load
+  constexpr int LPR = D / VEC;            // lanes per row
+  const ET* src = K + b * sb + h * sh;
+  for (int i = t; i < nt * LPR; i += 256) {
+    const int r = i / LPR, c = i % LPR;
+    const uint4 v = *reinterpret_cast<const uint4*>(src + (long long)(n0 + r) * sn + c * VEC);
+    *reinterpret_cast<uint4*>(&tile[r][c * VEC]) = v;
+  }
+  __syncthreads();
+
+  ET* dst = Kp + ((long long)row * F) * n_cap * 2;
+  for (int i = t; i < F * kPackTile; i += 256) {
+    const int f = i / kPackTile, r = i % kPackTile;
+    if (r < nt) {
+      const int d0 = fcs[f];
+      ET* o = dst + ((long long)f * n_cap + (n0 + r)) * 2;
+      o[0] = tile[r][d0];
+      o[1] = tile[r][d0 + D / 2];
+    }
+  }
+}
+
+// grid = (kHistBins / 1024, rows).  Every block clears 1024 histogram bins of its row; block x == 0
+// also clears the row counters and, when k_new is given, writes the new token (position n_ctx - 1)
+// into K, V and the packed planes.
+template <typename ET>
+__global__ __launch_bounds__(256) void prologue_kernel(uint32_t* __restrict__ hist,
+                                                       RowCtl* __restrict__ ctl, ET* __restrict__ K,
+                                                       ET* __restrict__ V, ET* __restrict__ Kp,
+                                                       const int32_t* __restrict__ fc_idx,
+                                                       const ET* __restrict__ k_new,
+                                                       const ET* __restrict__ v_new, int Hkv, int F,
+                                                       int n_cap, int n_ctx, long long sb,
+                                                       long long sh, long long sn) {
+  constexpr int D = kHeadDim;
+  const int row = blockIdx.y;
+  const int t = threadIdx.x;
+  reinterpret_cast<uint4*>(hist + (size_t)row * kHistBins + blockIdx.x * 1024)[t] = make_uint4(0, 0, 0, 0);
+  if (blockIdx.x != 0) return;
+  if (t == 0) ctl[row] = RowCtl{0u, 0u, 0u, 0u};
+  if (k_new == nullptr) return;
+  const int b = row / Hkv, h = row % Hkv;
+  const int n = n_ctx - 1;
+  const ET* ks = k_new + (size_t)row * D;
+  const ET* vs = v_new + (size_t)row * D;
+  if (t < D) {
+    K[b * sb + h * sh + (long long)n * sn + t] = ks[t];
+  } else if (t < 2 * D) {
+    V[b * sb + h * sh + (long long)n * sn + (t - D)] = vs[t - D];
+  }
+  if (t < F) {
+    const int d0 = fc_idx[h * F + t];
+    ET* o = Kp + (((long long)row * F + t) * n_cap + n) * 2;
+    o[0] = ks[d0];
+    o[1] = ks[d0 + D / 2];
+  }
+}
+
+hipError_t launch_pack(const fasa_shape& s, const void* K, const int32_t* fc_idx, void* Kp,
+                       int n_begin, int n_end, hipStream_t st) {
+  const int rows = s.batch * s.n_kv_heads;
+  dim3 grid((n_end - n_begin + kPackTile - 1) / kPackTile, rows), block(256);
+  if (s.dtype == FASA_BF16)
+    return launch("fasa_pack", pack_kernel<uint16_t>, grid, block, st, (const uint16_t*)K, fc_idx,
+                  (uint16_t*)Kp, s.n_kv_heads, s.n_fc, s.n_cap, n_begin, n_end,
+                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+  return launch("fasa_pack", pack_kernel<float>, grid, block, st, (const float*)K, fc_idx,
+                (float*)Kp, s.n_kv_heads, s.n_fc, s.n_cap, n_begin, n_end,
+                (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+}
+
+hipError_t launch_prologue(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, void* K, void* V,
+                           void* Kp, const int32_t* fc_idx, const void* k_new, const void* v_new,
+                           hipStream_t st) {
+  const int rows = s.batch * s.n_kv_heads;
+  dim3 grid(kHistBins / 1024, rows), block(256);
+  if (s.dtype == FASA_BF16)
+    return launch("fasa_prologue", prologue_kernel<uint16_t>, grid, block, st, hist, ctl,
+                  (uint16_t*)K, (uint16_t*)V, (uint16_t*)Kp, fc_idx, (const uint16_t*)k_new,
+                  (const uint16_t*)v_new, s.n_kv_heads, s.n_fc, s.n_cap, s.n_ctx,
+                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+  return launch("fasa_prologue", prologue_kernel<float>, grid, block, st, hist, ctl, (float*)K,
+                (float*)V, (float*)Kp, fc_idx, (const float*)k_new, (const float*)v_new,
+                s.n_kv_heads, s.n_fc, s.n_cap, s.n_ctx, (long long)s.kv_stride_b,
+                (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+}
+
+}  // namespace fasa

@@ -1,0 +1,178 @@
+// TIP scoring (paper Sec. 4.1): S = (sum over the GQA group of q^dom) . k^dom for every cached
+// token, streamed from the FC-major packed copy Kp; optionally also the coarse per-row histogram
+// of the order-preserving score keys that the selection stage starts from.
+#include "fasa_device.h"
+#include "fasa_internal.h"
+
+namespace fasa {
+
+template <typename ET> struct ScoreTraits;
+template <> struct ScoreTraits<uint16_t> { static constexpr int TPT = 4; };  // tokens per 16-byte load
+template <> struct ScoreTraits<float> { static constexpr int TPT = 2; };
+
+template <typename ET>
+__device__ __forceinline__ void fma_pairs(const uint4& w, float qlo, float qhi, float* acc);
+
+template <>
+__device__ __forceinline__ void fma_pairs<uint16_t>(const uint4& w, float qlo, float qhi, float* acc) {
+  acc[0] = fmaf(qhi, bf16_hi(w.x), fmaf(qlo, bf16_lo(w.x), acc[0]));
+  acc[1] = fmaf(qhi, bf16_hi(w.y), fmaf(qlo, bf16_lo(w.y), acc[1]));
+  acc[2] = fmaf(qhi, bf16_hi(w.z), fmaf(qlo, bf16_lo(w.z), acc[2]));
+  acc[3] = fmaf(qhi, bf16_hi(w.w), fmaf(qlo, bf16_lo(w.w), acc[3]));
+}
+
+template <>
+__device__ __forceinline__ void fma_pairs<float>(const uint4& w, float qlo, float qhi, float* acc) {
+  acc[0] = fmaf(qhi, __uint_as_float(w.y), fmaf(qlo, __uint_as_float(w.x), acc[0]));
+  acc[1] = fmaf(qhi, __uint_as_float(w.w), fmaf(qlo, __uint_as_float(w.z), acc[1]));
+}
+
+// grid = (ceil(N / (256 * TPT)), rows); one 16-byte load per thread per FC plane: a wave reads
+// 1 KiB contiguous from each of the F planes, F independent loads in flight per lane.
+template <typename ET, bool HIST>
+__global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
+                                                    const ET* __restrict__ Kp,
+                                                    const int32_t* __restrict__ fc_idx,
+                                                    float* __restrict__ S,
+                                                    uint32_t* __restrict__ hist, int Hq, int Hkv,
+                                                    int F, int N, int n_cap) {
+  constexpr int D = kHeadDim;
+  constexpr int TPT = ScoreTraits<ET>::TPT;
+  __shared__ float2 qs[D / 2];
+  __shared__ uint32_t lh[HIST ? kHistBins : 1];
+
+  const int row = blockIdx.y;
+  const int b = row / Hkv, h = row % Hkv;
+  const int G = Hq / Hkv;
+  const int t = threadIdx.x;
+
+  if (t < F) {
+    // group-summed dominant query components: sum_g (q_g . k) = (sum_g q_g) . k
+    const int i = fc_idx[h * F + t];
+    float lo = 0.f, hi = 0.f;
+    for (int g = 0; g < G; ++g) {
+      const ET* qh = q + ((size_t)b * Hq + (size_t)h * G + g) * D;
+      if constexpr (sizeof(ET) == 2) {
+        lo += __uint_as_float((uint32_t)qh[i] << 16);
+        hi += __uint_as_float((uint32_t)qh[i + D / 2] << 16);
+      } else {
+        lo += qh[i];
+        hi += qh[i + D / 2];
+      }
+    }
+    qs[t] = make_float2(lo, hi);
+  }
+  if constexpr (HIST) {
+    for (int i = t; i < kHistBins; i += 256) lh[i] = 0;
+  }
+  __syncthreads();
+
+  const int n0 = (blockIdx.x * 256 + t) * TPT;
+  if (n0 < N) {
+    const ET* p = Kp + ((size_t)row * F * n_cap + n0) * 2;
+    const size_t plane = (size_t)n_cap * 2;
+    float acc[TPT];
+#pragma unroll
+    for (int k = 0; k < TPT; ++k) acc[k] = 0.f;
+    int f = 0;
+    for (; f + 8 <= F; f += 8) {
+      uint4 w[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) w[u] = *reinterpret_cast<const uint4*>(p + (size_t)(f + u) * plane);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float2 qf = qs[f + u];
+        fma_pairs<ET>(w[u], qf.x, qf.y, acc);
+      }
+    }
+    for (; f < F; ++f) {
+      const uint4 w = *reinterpret_cast<const uint4*>(p + (size_t)f * plane);
+      const float2 qf = qs[f];
+      fma_pairs<ET>(w, qf.x, qf.y, acc);
+    }
+    float* out = S + (size_t)row * n_cap + n0;
+    if (n0 + TPT <= N) {
+      if constexpr (TPT == 4) *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+      else *reinterpret_cast<float2*>(out) = make_float2(acc[0], acc[1]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < TPT; ++k)
+        if (n0 + k < N) out[k] = acc[k];
+    }
+    if constexpr (HIST) {
+#pragma unroll
+      for (int k = 0; k < TPT; ++k)
+        if (n0 + k < N) atomicAdd(&lh[score_key(acc[k]) >> kKeyLowBits], 1u);
+    }
+  }
+  if constexpr (HIST) {
+    __syncthreads();
+    uint32_t* gh = hist + (size_t)row * kHistBins;
+    for (int i = t; i < kHistBins; i += 256) {
+      const uint32_t c = lh[i];
+      if (c) atomicAdd(&gh[i], c);
+    }
+  }
+}
+
+// Histogram of an existing score vector (stand-alone fasa_topk).  grid = (ceil(N / 4096), rows).
+__global__ __launch_bounds__(256) void hist_kernel(const float* __restrict__ S,
+                                                   uint32_t* __restrict__ hist, int N, int n_cap) {
+  __shared__ uint32_t lh[kHistBins];
+  const int row = blockIdx.y;
+  const int t = threadIdx.x;
+  for (int i = t; i < kHistBins; i += 256) lh[i] = 0;
+  __syncthreads();
+  const float* s = S + (size_t)row * n_cap;
+  const int base = blockIdx.x * 4096;
+  for (int it = 0; it < 4; ++it) {
+    const int n0 = base + (it * 256 + t) * 4;
+    if (n0 + 4 <= N) {
+      const float4 v = *reinterpret_cast<const float4*>(s + n0);
+      atomicAdd(&lh[score_key(v.x) >> kKeyLowBits], 1u);
+      atomicAdd(&lh[score_key(v.y) >> kKeyLowBits], 1u);
+      atomicAdd(&lh[score_key(v.z) >> kKeyLowBits], 1u);
+      atomicAdd(&lh[score_key(v.w) >> kKeyLowBits], 1u);
+    } else {
+      for (int k = 0; k < 4; ++k)
+        if (n0 + k < N) atomicAdd(&lh[score_key(s[n0 + k]) >> kKeyLowBits], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = hist + (size_t)row * kHistBins;
+  for (int i = t; i < kHistBins; i += 256) {
+    const uint32_t c = lh[i];
+    if (c) atomicAdd(&gh[i], c);
+  }
+}
+
+hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
+                        float* S, uint32_t* hist, hipStream_t st) {
+  const int rows = s.batch * s.n_kv_heads;
+  dim3 block(256);
+  if (s.dtype == FASA_BF16) {
+    dim3 grid((s.n_ctx + 1023) / 1024, rows);
+    if (hist)
+      return launch("fasa_score_hist", score_kernel<uint16_t, true>, grid, block, st,
+                    (const uint16_t*)q, (const uint16_t*)Kp, fc_idx, S, hist, s.n_q_heads,
+                    s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap);
+    return launch("fasa_score", score_kernel<uint16_t, false>, grid, block, st, (const uint16_t*)q,
+                  (const uint16_t*)Kp, fc_idx, S, hist, s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx,
+                  s.n_cap);
+  }
+  dim3 grid((s.n_ctx + 511) / 512, rows);
+  if (hist)
+    return launch("fasa_score_hist", score_kernel<float, true>, grid, block, st, (const float*)q,
+                  (const float*)Kp, fc_idx, S, hist, s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx,
+                  s.n_cap);
+  return launch("fasa_score", score_kernel<float, false>, grid, block, st, (const float*)q,
+                (const float*)Kp, fc_idx, S, hist, s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx,
+                s.n_cap);
+}
+
+hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st) {
+  dim3 grid((s.n_ctx + 4095) / 4096, s.batch * s.n_kv_heads), block(256);
+  return launch("fasa_hist", hist_kernel, grid, block, st, S, hist, s.n_ctx, s.n_cap);
+}
+
+}  // namespace fasa

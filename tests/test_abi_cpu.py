@@ -1,0 +1,141 @@
+"""The C-ABI library on a host without a GPU: it loads, exports every symbol the header declares,
+and validates arguments before any HIP call (error codes, never a crash)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2602_03152_amd", "libfasa.so")
+
+if not os.path.exists(LIB):   # build once if the tree is fresh (the GPU tests load what is built)
+    from paper_2602_03152_amd import build as _build
+    _build.build(verbose=False)
+
+from paper_2602_03152_amd import binding as fb  # noqa: E402
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "fasa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fasa_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = _declared()
+    assert len(names) >= 15 and "fasa_decode_step" in names and "fasa_pack_kcache" in names
+    lib = C.CDLL(LIB)
+    for n in names:
+        assert hasattr(lib, n), n
+        assert hasattr(fb, n), "binding lacks %s" % n
+    assert sorted(fb.EXPORTS) == names
+
+
+def _shape(**kw):
+    base = dict(batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, n_fc=16, n_ctx=1000, n_cap=1024,
+                budget=100, dtype="bf16")
+    base.update(kw)
+    return fb.make_shape(**base)
+
+
+def test_version_and_strerror():
+    assert fb.fasa_version() >= 1000
+    assert fb.fasa_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert len(fb.fasa_strerror(code)) > 3
+
+
+def test_workspace_bytes_is_pure_and_monotone():
+    a = fb.fasa_workspace_bytes(_shape())
+    assert a > 0 and a % 256 == 0 and a == fb.fasa_workspace_bytes(_shape())
+    assert fb.fasa_workspace_bytes(_shape(n_cap=4096, n_ctx=4000)) > a
+    assert fb.fasa_workspace_bytes(_shape(n_cap=1000)) == 0          # n_cap not a multiple of 64
+    assert fb.fasa_workspace_bytes(_shape(n_ctx=2000)) == 0          # n_ctx > n_cap
+    assert fb.fasa_workspace_bytes(_shape(budget=0)) == 0
+
+
+def test_validate_fc_idx():
+    s = _shape(n_fc=4)
+    ok = np.tile(np.array([0, 63, 5, 17], np.int32), (8, 1))
+    fb.fasa_validate_fc_idx(s, ok)
+    for bad in ([0, 64, 5, 17], [0, -1, 5, 17], [5, 63, 5, 17]):
+        arr = ok.copy(); arr[3] = bad
+        with pytest.raises(fb.FasaError) as e:
+            fb.fasa_validate_fc_idx(s, arr)
+        assert e.value.status == fb.FASA_EINVAL
+    with pytest.raises(fb.FasaError):
+        fb.fasa_validate_fc_idx(s, None)
+
+
+A = 0x10000   # a fake, 16-byte aligned "device pointer": validation must fail before it is touched
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(batch=0), fb.FASA_EINVAL),
+    (dict(n_q_heads=30), fb.FASA_EINVAL),              # not a multiple of n_kv_heads
+    (dict(head_dim=127), fb.FASA_EINVAL),
+    (dict(head_dim=64), fb.FASA_EUNSUPPORTED),
+    (dict(n_q_heads=72), fb.FASA_EUNSUPPORTED),        # GQA group 9
+    (dict(n_fc=0), fb.FASA_EINVAL),
+    (dict(n_fc=65), fb.FASA_EINVAL),
+    (dict(n_ctx=0), fb.FASA_EINVAL),
+    (dict(n_ctx=1025), fb.FASA_EINVAL),
+    (dict(budget=0), fb.FASA_EINVAL),
+    (dict(n_cap=1000), fb.FASA_EINVAL),
+    (dict(dtype=fb.FASA_F32, kv_stride_n=100), fb.FASA_EINVAL),
+    (dict(kv_stride_n=132), fb.FASA_EINVAL),           # not a multiple of 8 elements
+])
+def test_decode_step_rejects_bad_shapes(kw, code):
+    s = _shape(**kw)
+    if "dtype" in kw and kw["dtype"] == fb.FASA_F32:
+        pass
+    rc = fb.lib.fasa_decode_step(C.byref(s), A, A, A, A, A, None, None, A, A, A, A, 1 << 40, None)
+    assert rc == code
+
+
+def test_reserved_field_must_be_zero():
+    s = _shape(); s.reserved = 1
+    assert fb.lib.fasa_score(C.byref(s), A, A, A, A, None) == fb.FASA_EINVAL
+
+
+def test_null_and_misaligned_pointers():
+    s = _shape()
+    L = fb.lib
+    assert L.fasa_score(C.byref(s), None, A, A, A, None) == fb.FASA_EINVAL
+    assert L.fasa_score(C.byref(s), A, A + 4, A, A, None) == fb.FASA_EINVAL
+    assert L.fasa_score(None, A, A, A, A, None) == fb.FASA_EINVAL
+    assert L.fasa_pack_kcache(C.byref(s), A, A, None, 0, 10, None) == fb.FASA_EINVAL
+    assert L.fasa_pack_kcache(C.byref(s), A, A, A, 10, 5, None) == fb.FASA_EINVAL
+    assert L.fasa_pack_kcache(C.byref(s), A, A, A, 0, 1025, None) == fb.FASA_EINVAL
+    assert L.fasa_pack_kcache(C.byref(s), A, A, A, 7, 7, None) == fb.FASA_OK      # empty range: nothing to do
+    assert L.fasa_topk(C.byref(s), A, A + 8, A, 1 << 40, None) == fb.FASA_EINVAL
+    assert L.fasa_topk(C.byref(s), A, A, None, 1 << 40, None) == fb.FASA_EINVAL
+    assert L.fasa_sparse_attend(C.byref(s), A, A, A, None, A, A, 1 << 40, None) == fb.FASA_EINVAL
+    assert L.fasa_dense_attend(C.byref(s), A, A, None, A, A, 1 << 40, None) == fb.FASA_EINVAL
+    # k_new without v_new
+    assert L.fasa_decode_step(C.byref(s), A, A, A, A, A, A, None, A, A, A, A, 1 << 40, None) == fb.FASA_EINVAL
+
+
+def test_workspace_too_small():
+    s = _shape()
+    need = fb.fasa_workspace_bytes(s)
+    L = fb.lib
+    assert L.fasa_topk(C.byref(s), A, A, A, need - 1, None) == fb.FASA_EWORKSPACE
+    assert L.fasa_sparse_attend(C.byref(s), A, A, A, A, A, A, 16, None) == fb.FASA_EWORKSPACE
+    assert L.fasa_decode_step(C.byref(s), A, A, A, A, A, None, None, A, A, A, A, 0, None) == fb.FASA_EWORKSPACE
+
+
+def test_binding_raises():
+    s = _shape(budget=0)
+    with pytest.raises(fb.FasaError) as e:
+        fb.fasa_topk(s, A, A, A, 1 << 40, stream=0)
+    assert e.value.status == fb.FASA_EINVAL and "invalid" in str(e.value)
+
+
+def test_profile_api_without_launches():
+    fb.fasa_profile_reset()
+    fb.fasa_profile_enable(False)
+    buf = C.create_string_buffer(8)
+    assert fb.lib.fasa_profile_entry(0, buf, 8, None, None) == fb.FASA_EINVAL

@@ -1,0 +1,208 @@
+"""GPU parity of the fused decode step (TIP -> TopK-I -> FAC in one call) against the CPU oracle,
+at reduced sizes that span several tiles with ragged tails, and at the full benchmark sizes."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fasa_oracle as O
+from paper_2602_03152_amd import workload as W
+
+pytestmark = pytest.mark.gpu
+
+SCORE_RTOL = 1e-5
+OUT_ATOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def fb():
+    from paper_2602_03152_amd import binding
+    return binding
+
+
+def check_selection(S_ref, D_ref, T_gpu, budget, n_ctx):
+    """The selected set must contain every token whose oracle score clears the oracle's B-th
+    score by more than the band and none that falls short of it by more than the band;
+    band = 1e-5 * max(|tau|, max_n D[n]) (the score tolerance, applied at the threshold).
+    Returns the number of tokens on which the set differs from the oracle's own."""
+    bsel = min(budget, n_ctx)
+    n_diff = 0
+    for b in range(S_ref.shape[0]):
+        for h in range(S_ref.shape[1]):
+            s = S_ref[b, h, :n_ctx]
+            t = np.asarray(T_gpu[b, h])
+            assert t.shape == (bsel,)
+            assert t.min() >= 0 and t.max() < n_ctx
+            assert len(np.unique(t)) == bsel, "duplicates in the index set"
+            ref = O.topk_indices(s.astype(np.float32), budget)
+            tau = np.sort(s)[n_ctx - bsel]
+            band = SCORE_RTOL * max(abs(tau), float(D_ref[b, h, :n_ctx].max()))
+            sel = np.zeros(n_ctx, bool); sel[t] = True
+            must = s > tau + band
+            must_not = s < tau - band
+            assert sel[must].all(), "a clear winner is missing"
+            assert not sel[must_not].any(), "a clear loser was selected"
+            n_diff += int(np.setdiff1d(ref, t).size)
+    return n_diff
+
+
+def run_step(fb, w, x, d=None, k_new=None, v_new=None, q=None, n_ctx=None, budget=None):
+    from tests.gpu_util import Device, to_dev
+    if d is None:
+        d = Device(w, x)
+        d.pack()
+    shape = d.make_shape(n_ctx=n_ctx, budget=budget)
+    qd = d.q if q is None else to_dev(q)
+    kd = None if k_new is None else to_dev(k_new)
+    vd = None if v_new is None else to_dev(v_new)
+    fb.fasa_decode_step(shape, qd, d.K, d.V, d.Kp, d.fc_idx, kd, vd, d.S, d.T, d.O, d.ws, d.ws_bytes)
+    torch.cuda.synchronize()
+    return d
+
+
+def compare_step(w, x_host_q, K, V, fc_idx, d, n_ctx, budget, rows=None):
+    """Oracle vs device outputs for the (sub)set of batch entries `rows`."""
+    from tests.gpu_util import to_host
+    bsel = min(budget, n_ctx)
+    bs = list(range(w.batch)) if rows is None else rows
+    q = x_host_q[bs]
+    S_ref, D_ref = O.score(q, K[bs], fc_idx, n_ctx)
+    S = to_host(d.S)[bs][:, :, :n_ctx].astype(np.float64)
+    err = np.abs(S - S_ref)
+    assert np.all(err <= SCORE_RTOL * np.maximum(np.abs(S_ref), D_ref))
+    # T is [batch][n_kv_heads][bsel] packed at the front of the buffer (row pitch = bsel of this call)
+    T = to_host(d.T).reshape(-1)[: w.batch * w.n_kv_heads * bsel].reshape(w.batch, w.n_kv_heads, bsel)[bs]
+    n_diff = check_selection(S_ref, D_ref, T, budget, n_ctx)
+    O_ref = O.sparse_attend(q, K[bs], V[bs], T)          # oracle FAC on the device's validated set
+    o_err = np.abs(to_host(d.O)[bs].astype(np.float64) - O_ref).max()
+    assert o_err <= OUT_ATOL, o_err
+    return n_diff, o_err
+
+
+REDUCED = {
+    "cfg0_full": dict(cid=0),
+    "cfg1_ragged": dict(cid=1, n_ctx=5000 + 19, budget=313),
+    "cfg2_small": dict(cid=2, batch=4, n_ctx=3001, budget=256),
+    "cfg3_gqa7": dict(cid=3, batch=2, n_ctx=4099, budget=W.budget_fraction(4099)),
+    "cfg4_small": dict(cid=4, n_ctx=10007, budget=80),
+    "budget_1": dict(cid=1, n_ctx=1000, budget=1),
+    "budget_eq_n": dict(cid=1, n_ctx=777, budget=777, n_kv_heads=2, n_q_heads=8),
+    "budget_gt_n": dict(cid=1, n_ctx=130, budget=4096, n_kv_heads=2, n_q_heads=8),
+    "n_1": dict(cid=1, n_ctx=1, budget=1, n_kv_heads=2, n_q_heads=4),
+    "f32_g1_ragged": dict(cid=0, n_ctx=2049, budget=65),
+}
+
+
+@pytest.mark.parametrize("name", list(REDUCED))
+def test_decode_step_reduced(fb, name):
+    kw = dict(REDUCED[name]); cid = kw.pop("cid")
+    w = W.WORKLOADS[cid].scaled(**kw)
+    x = W.make_inputs(w, n_cap=(w.n_ctx + 63) // 64 * 64)
+    print("decode_step", name, flush=True)
+    d = run_step(fb, w, x)
+    n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget)
+    print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
+
+
+def test_all_fcs_full_budget_is_dense_attention(fb):
+    """F = d/2 and B = N on the device: the fused step equals the oracle's dense attention and the
+    device's own dense kernel."""
+    from tests.gpu_util import to_host
+    w = W.WORKLOADS[1].scaled(n_ctx=1111, budget=1111, n_fc=64, n_kv_heads=2, n_q_heads=8)
+    x = W.make_inputs(w, n_cap=1152)
+    d = run_step(fb, w, x)
+    out = to_host(d.O).astype(np.float64)
+    ref = O.dense_attend(x["q"], x["K"], x["V"], w.n_ctx)
+    assert np.abs(out - ref).max() <= OUT_ATOL
+    S_full = np.einsum("bhgd,bhnd->bhn", W.storage_to_f64(x["q"]).reshape(1, 2, 4, 128), W.storage_to_f64(x["K"])[:, :, :1111])
+    assert np.abs(to_host(d.S)[:, :, :1111] - S_full).max() <= 1e-5 * np.abs(S_full).max() * 10
+    fb.fasa_dense_attend(d.shape, d.q, d.K, d.V, d.O, d.ws, d.ws_bytes)
+    torch.cuda.synchronize()
+    assert np.abs(to_host(d.O) - out).max() <= 1e-5
+
+
+def test_fused_equals_staged_calls(fb):
+    from tests.gpu_util import Device, to_host
+    w = W.WORKLOADS[1].scaled(n_ctx=6000 + 5, budget=500)
+    x = W.make_inputs(w, n_cap=6016)
+    d = run_step(fb, w, x)
+    S1, T1, O1 = to_host(d.S).copy(), np.sort(to_host(d.T), -1), to_host(d.O).copy()
+    e = Device(w, x)
+    e.pack()
+    fb.fasa_score(e.shape, e.q, e.Kp, e.fc_idx, e.S)
+    fb.fasa_topk(e.shape, e.S, e.T, e.ws, e.ws_bytes)
+    fb.fasa_sparse_attend(e.shape, e.q, e.K, e.V, e.T, e.O, e.ws, e.ws_bytes)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host(e.S)[:, :, :w.n_ctx], S1[:, :, :w.n_ctx])
+    np.testing.assert_array_equal(np.sort(to_host(e.T), -1), T1)
+    drift = float(np.abs(to_host(e.O) - O1).max())
+    assert drift <= 2e-5, drift
+
+
+def test_repeated_calls_on_one_workspace_are_stable(fb):
+    from tests.gpu_util import to_host
+    w = W.WORKLOADS[2].scaled(batch=2, n_ctx=4000, budget=256)
+    x = W.make_inputs(w, n_cap=4032)
+    d = run_step(fb, w, x)
+    T0, O0 = np.sort(to_host(d.T), -1), to_host(d.O).copy()
+    for _ in range(5):
+        run_step(fb, w, x, d=d)
+        np.testing.assert_array_equal(np.sort(to_host(d.T), -1), T0)
+        # the set is reproducible; its order in T (atomic append) is not, so the float32
+        # accumulation order of FAC may differ between runs by a few ulp
+        drift = float(np.abs(to_host(d.O) - O0).max())
+        assert drift <= 2e-5, drift
+
+
+def test_growing_cache_appends(fb):
+    """Long-CoT recipe at a reduced size: each step appends one K/V row (cache, packed copy) and
+    re-selects with B = 18.9% of the current length."""
+    from tests.gpu_util import Device, to_host
+    w = W.WORKLOADS[3].scaled(batch=2, n_ctx=3000, budget=W.budget_fraction(3000))
+    steps = 6
+    x = W.make_inputs(w, n_cap=3072)
+    K, V = x["K"].copy(), x["V"].copy()
+    d = Device(w, x)
+    d.T = torch.full((w.batch, w.n_kv_heads, W.budget_fraction(3000 + steps)), -1, dtype=torch.int32, device="cuda")
+    d.pack()
+    n = w.n_ctx
+    run_step(fb, w, x, d=d, n_ctx=n, budget=W.budget_fraction(n))
+    compare_step(w, x["q"], K, V, x["fc_idx"], d, n, W.budget_fraction(n))
+    for s in range(1, steps + 1):
+        a = W.make_append(w, x["fc_idx"], step=s, n_before=n)
+        K[:, :, n] = a["k_new"]; V[:, :, n] = a["v_new"]
+        n += 1
+        b = W.budget_fraction(n)
+        print("append step", s, "n", n, "budget", b, flush=True)
+        run_step(fb, w, x, d=d, k_new=a["k_new"], v_new=a["v_new"], q=a["q"], n_ctx=n, budget=b)
+        np.testing.assert_array_equal(to_host(d.K, np.uint16)[:, :, :n], K[:, :, :n])
+        np.testing.assert_array_equal(to_host(d.V, np.uint16)[:, :, :n], V[:, :, :n])
+        np.testing.assert_array_equal(to_host(d.Kp, np.uint16)[:, :, :, :n], O.pack_kcache(K, x["fc_idx"], n))
+        compare_step(w, a["q"], K, V, x["fc_idx"], d, n, b)
+
+
+# ------------------------------------------------------------------------------------------------
+# full benchmark sizes, in the launch configuration the bench times
+# ------------------------------------------------------------------------------------------------
+def test_full_size_config1(fb):
+    w = W.WORKLOADS[1]
+    x = W.make_inputs(w)
+    print("full config 1", flush=True)
+    d = run_step(fb, w, x)
+    n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget)
+    print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
+    from tests.gpu_util import to_host
+    fb.fasa_dense_attend(d.shape, d.q, d.K, d.V, d.O, d.ws, d.ws_bytes)
+    torch.cuda.synchronize()
+    ref = O.dense_attend(x["q"], x["K"], x["V"], w.n_ctx)
+    assert np.abs(to_host(d.O) - ref).max() <= OUT_ATOL
+
+
+@pytest.mark.parametrize("cid,rows", [(2, [0, 7, 15]), (4, None), (3, [0, 5])])
+def test_full_size_sampled(fb, cid, rows):
+    """Configs 2-4 at full size; the oracle checks a sample of the batch entries (all of config 4)."""
+    w = W.WORKLOADS[cid]
+    x = W.make_inputs(w)
+    print("full config", cid, flush=True)
+    d = run_step(fb, w, x)
+    n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget, rows=rows)
+    print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
