@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the FASA decode hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
+
+A "step" is one fasa_decode_step (score -> top-k -> sparse attention) over one batch of synthetic,
+HBM-resident input shaped like the chosen workload (default: the Llama-3-8B-shaped layer at 32k
+context, budget 2048, 16 dominant FCs).  The step rotates over R independent buffer sets so that the
+bytes a step touches have left the 256 MB last-level cache before their set comes round again.
+
+Three passes, all inside this process:
+  timed     W warm-up + exactly K steps replayed from a captured HIP graph (one graph = one step on
+            each of the R buffer sets), bracketed by synchronize; `value` = microseconds per step.
+            The same K steps launched eagerly are timed too and reported as `eager_us_per_step`.
+  kernels   the same K steps launched eagerly with the library's per-kernel timestamps on: average
+            GPU execution time of every kernel of the path -> the `roofline` object of the dominant
+            kernel and the `kernels` table.
+  baselines the library's own full-KV decode kernel on the same buffers (`dense_baseline`) and the
+            CPU oracle timed on the host cores (`cpu_baseline`).
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E bandwidth
+LLC_BYTES = 256 << 20         # last-level (memory-side) cache the rotation has to defeat
+
+# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
+# what the same counters read for a plain copy kernel of known size (see profiles/).  Keyed by
+# (workload config id, kernel name); bytes per launch.  None = not measured yet.
+MEASURED_TRAFFIC = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=240)
+    ap.add_argument("--warmup", type=int, default=24)
+    ap.add_argument("--config", type=int, default=1, help="workload id (0-4); the metric is quoted on 1")
+    ap.add_argument("--sets", type=int, default=0, help="buffer sets to rotate over (0 = derive)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the hot path shards by batch / KV head with no "
+                 "exchange; no multi-GPU path exists here). Re-run with --gpus 1.")
+
+    import numpy as np
+    import torch
+
+    from paper_2602_03152_amd import binding as fb      # raises if libfasa.so is missing
+    from paper_2602_03152_amd import workload as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = W.WORKLOADS[args.config]
+    rows = w.batch * w.n_kv_heads
+    model = W.algorithmic_bytes(w)
+    bsel = min(w.budget, w.n_ctx)
+
+    # ---------------- inputs: one seeded draw, cloned into R device-resident sets ----------------
+    t0 = time.time()
+    x = W.make_inputs(w)
+    log("inputs drawn in %.1fs" % (time.time() - t0))
+    n_cap = x["n_cap"]
+    tdt = torch.int16 if w.dtype == "bf16" else torch.float32
+    touched = model["alg_plus_intermediates"]
+    R = args.sets or max(4, min(64, int(np.ceil(2.5 * LLC_BYTES / touched))))
+    K_steps = max(R, (args.steps // R) * R) if not args.no_graph else args.steps
+    dev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_fc, w.n_ctx, n_cap, w.budget, w.dtype)
+    ws_bytes = fb.fasa_workspace_bytes(shape)
+    q0, K0, V0, fc = dev(x["q"]), dev(x["K"]), dev(x["V"]), dev(x["fc_idx"])
+    sets = []
+    for r in range(R):
+        s = {
+            "q": q0.clone(), "K": K0 if r == 0 else K0.clone(), "V": V0 if r == 0 else V0.clone(),
+            "Kp": torch.zeros((w.batch, w.n_kv_heads, w.n_fc, n_cap, 2), dtype=tdt, device="cuda"),
+            "S": torch.zeros((w.batch, w.n_kv_heads, n_cap), dtype=torch.float32, device="cuda"),
+            "T": torch.zeros((w.batch, w.n_kv_heads, bsel), dtype=torch.int32, device="cuda"),
+            "O": torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda"),
+            "ws": torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda"),
+        }
+        fb.fasa_workspace_init(shape, s["ws"], ws_bytes)
+        fb.fasa_pack_kcache(shape, s["K"], fc, s["Kp"], 0, w.n_ctx)
+        sets.append(s)
+    torch.cuda.synchronize()
+    log("workload %s: R=%d buffer sets, %.1f MB touched per step, %.2f GB resident"
+        % (w.name, R, touched / 1e6, torch.cuda.memory_allocated() / 1e9))
+
+    def step(s):
+        fb.fasa_decode_step(shape, s["q"], s["K"], s["V"], s["Kp"], fc, None, None,
+                            s["S"], s["T"], s["O"], s["ws"], ws_bytes)
+
+    def dense(s):
+        fb.fasa_dense_attend(shape, s["q"], s["K"], s["V"], s["O"], s["ws"], ws_bytes)
+
+    def time_loop(fn, n_steps, warm):
+        for i in range(warm):
+            fn(sets[i % R])
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(n_steps):
+            fn(sets[i % R])
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n_steps * 1e3          # us per step
+
+    # ---------------- pass 1: timed region ----------------
+    eager_us = time_loop(step, K_steps, args.warmup)
+    log("eager: %.2f us/step" % eager_us)
+    ref_T = np.sort(sets[0]["T"].cpu().numpy(), -1)
+    ref_O = sets[0]["O"].cpu().numpy().copy()
+    graph_us, mode = None, "eager"
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(sets[0])
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for s in sets:
+                step(s)
+        torch.cuda.synchronize()
+        for _ in range(max(1, args.warmup // R)):
+            g.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(K_steps // R):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        graph_us = a.elapsed_time(b) / K_steps * 1e3
+        # every replay must reproduce the eager result (same set; output within accumulation-order noise)
+        ok = True
+        for _ in range(3):
+            g.replay()
+            torch.cuda.synchronize()
+            ok &= bool(np.array_equal(np.sort(sets[0]["T"].cpu().numpy(), -1), ref_T))
+            ok &= bool(np.abs(sets[0]["O"].cpu().numpy() - ref_O).max() <= 2e-5)
+            step(sets[1]); torch.cuda.synchronize()
+        log("graph: %.2f us/step, replays match eager: %s" % (graph_us, ok))
+        if ok and graph_us < eager_us:
+            mode = "hipgraph"
+    us_per_step = graph_us if mode == "hipgraph" else eager_us
+
+    # ---------------- pass 2: per-kernel GPU time ----------------
+    fb.fasa_profile_reset()
+    fb.fasa_profile_enable(True)
+    for i in range(K_steps):
+        step(sets[i % R])
+    prof = fb.profile_summary()
+    fb.fasa_profile_reset()
+    for i in range(K_steps):
+        dense(sets[i % R])
+    prof_dense = fb.profile_summary()
+    fb.fasa_profile_enable(False)
+    fb.fasa_profile_reset()
+
+    e = w.elem_bytes
+    alg_bytes = {   # algorithmic bytes per launch of each kernel (what the method itself must move)
+        "fasa_score_hist": rows * w.n_ctx * 2 * w.n_fc * e,
+        "fasa_select": rows * w.n_ctx * 4,
+        "fasa_sparse_attend": rows * 2 * bsel * w.head_dim * e,
+        "fasa_dense_attend": rows * 2 * w.n_ctx * w.head_dim * e,
+    }
+    kernels = {}
+    for name, (launches, ms) in {**prof, **prof_dense}.items():
+        us = ms / launches * 1e3
+        ent = {"launches": launches, "avg_us": round(us, 3)}
+        if name in alg_bytes:
+            ent["alg_bytes"] = alg_bytes[name]
+            ent["gbps"] = round(alg_bytes[name] / us / 1e3, 1)
+        kernels[name] = ent
+    path_kernels = [k for k in prof if k in alg_bytes]
+    dom = max(path_kernels, key=lambda k: alg_bytes[k])      # the kernel that moves the most bytes
+    dom_us = prof[dom][1] / prof[dom][0] * 1e3
+    achieved = alg_bytes[dom] / dom_us / 1e3
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": MEASURED_TRAFFIC.get((w.config_id, dom))}
+    sum_kernel_us = sum(prof[k][1] / prof[k][0] * 1e3 for k in prof)
+
+    dense_us = time_loop(dense, K_steps, args.warmup)
+    dense_kernel_us = sum(ms / n * 1e3 for n, ms in prof_dense.values())
+    log("dense full-KV decode: %.2f us/step" % dense_us)
+
+    # ---------------- pass 3: CPU oracle on the host cores ----------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import fasa_oracle as O
+        sub = list(range(w.batch)) if w.batch <= 2 else [0]          # bounded sample of the batch
+        qs, Ks, Vs = x["q"][sub], x["K"][sub], x["V"][sub]
+        reps, t_cpu0, c0 = 0, time.time(), time.process_time()
+        while True:
+            O.decode_step(qs, Ks, Vs, x["fc_idx"], w.n_ctx, w.budget)
+            reps += 1
+            if time.time() - t_cpu0 >= 10.0 or reps >= 200:
+                break
+        wall, cpu_t = time.time() - t_cpu0, time.process_time() - c0
+        per_step = wall / reps * (w.batch / len(sub))
+        cpu = {"value": round(per_step * 1e6, 1), "unit": "us", "cores": max(1, int(round(cpu_t / wall))),
+               "kind": "oracle",
+               "sample": "%d full oracle decode steps on %d of %d batch entries, scaled to the batch; "
+                         "numpy float64" % (reps, len(sub), w.batch)}
+        log("cpu oracle: %.0f us/step (%d reps)" % (cpu["value"], reps))
+
+    out = {
+        "metric": "us_per_decode_step", "value": round(us_per_step, 3), "unit": "us",
+        "n_gpus": 1, "steps": K_steps, "warmup": args.warmup, "ms_per_step": round(us_per_step / 1e3, 6),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "n_ctx": w.n_ctx, "budget": bsel, "n_fc": w.n_fc,
+                   "storage_dtype": w.dtype, "buffer_sets": R, "launch": mode},
+        "hbm": {"alg_bytes": model["alg"], "alg_plus_intermediate_bytes": model["alg_plus_intermediates"],
+                "step_gbps": round(model["alg"] / us_per_step / 1e3, 1),
+                "step_frac_of_peak": round(model["alg"] / us_per_step / 1e3 / HBM_PEAK_GBPS, 4),
+                "kernel_time_gbps": round(model["alg"] / sum_kernel_us / 1e3, 1),
+                "kernel_time_frac_of_peak": round(model["alg"] / sum_kernel_us / 1e3 / HBM_PEAK_GBPS, 4)},
+        "eager_us_per_step": round(eager_us, 3),
+        "graph_us_per_step": None if graph_us is None else round(graph_us, 3),
+        "sum_kernel_us": round(sum_kernel_us, 3),
+        "roofline": roofline,
+        "kernels": kernels,
+        "dense_baseline": {"us_per_step": round(dense_us, 3), "kernel_us": round(dense_kernel_us, 3),
+                           "bytes": model["dense"], "gbps": round(model["dense"] / dense_us / 1e3, 1),
+                           "speedup_of_fasa": round(dense_us / us_per_step, 3)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

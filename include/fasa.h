@@ -11,6 +11,7 @@
  * Conventions that hold for every entry point
  *   - All tensor pointers are DEVICE pointers (HBM) unless the name ends in _host.  The caller owns
  *     every buffer, including the workspace; the library allocates and frees nothing on the device.
+ *     A workspace is prepared once with fasa_workspace_init and then reused call after call.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream).  No entry
  *     point synchronises the host.  Calls that share a workspace must be ordered by the stream.
  *   - Return value: FASA_OK (0) or a negative fasa_status.  Arguments are validated before the
@@ -72,6 +73,15 @@ typedef struct fasa_shape {
  * Returns 0 if the shape is invalid. */
 size_t fasa_workspace_bytes(const fasa_shape* shape);
 
+/* Prepares a workspace: zeroes the counters and histograms the selection and attention stages
+ * count in.  Call once after allocating (or after anything else wrote to) the workspace, and again
+ * after a call that returned an error.  Every successful fasa_topk / fasa_sparse_attend /
+ * fasa_dense_attend / fasa_decode_step leaves the workspace prepared for the next call, so a decode
+ * loop initialises once.  The workspace layout depends on batch * n_kv_heads only for the part
+ * that must be zero, so one prepared workspace serves calls whose n_ctx and budget vary, as long
+ * as it is at least fasa_workspace_bytes() of each call's shape. */
+int fasa_workspace_init(const fasa_shape* shape, void* ws, size_t ws_bytes, void* stream);
+
 /* Host-side check of a dominant-FC list (HOST pointer [n_kv_heads][n_fc]): every value in
  * [0, head_dim/2), no duplicates within a head (an FC is selected whole or not at all,
  * paper App. D.2). */
@@ -93,7 +103,7 @@ int fasa_score(const fasa_shape* shape, const void* q, const void* Kp, const int
 
 /* TopK-I (paper Sec. 4.1, T_t = TopK-I(S_t, N_fac)): for each (b,h) the index set of the
  * min(budget, n_ctx) largest S[b,h,0:n_ctx].  Equal scores are resolved towards the lower index;
- * -0 and +0 are equal.  Uses and overwrites the workspace. */
+ * -0 and +0 are equal.  Needs a prepared workspace (fasa_workspace_init) and leaves it prepared. */
 int fasa_topk(const fasa_shape* shape, const float* S, int32_t* T, void* ws, size_t ws_bytes,
               void* stream);
 

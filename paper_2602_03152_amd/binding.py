@@ -11,13 +11,17 @@ import ctypes as C
 import os
 from typing import Optional
 
+# torch first: it brings its own HIP runtime (libamdhip64.so.7); libfasa.so asks for the same
+# soname and must bind to the copy torch's allocator and streams live in, not to a second one.
+import torch  # noqa: F401
+
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfasa.so")
 
 FASA_OK, FASA_EINVAL, FASA_EUNSUPPORTED, FASA_EWORKSPACE, FASA_EHIP = 0, -1, -2, -3, -4
 FASA_BF16, FASA_F32 = 0, 1
 
 EXPORTS = [
-    "fasa_workspace_bytes", "fasa_validate_fc_idx", "fasa_pack_kcache", "fasa_score", "fasa_topk",
+    "fasa_workspace_bytes", "fasa_workspace_init", "fasa_validate_fc_idx", "fasa_pack_kcache", "fasa_score", "fasa_topk",
     "fasa_sparse_attend", "fasa_dense_attend", "fasa_decode_step", "fasa_strerror",
     "fasa_last_hip_error", "fasa_version", "fasa_profile_enable", "fasa_profile_reset",
     "fasa_profile_collect", "fasa_profile_entry",
@@ -50,6 +54,7 @@ def _load():
     P, I32, SZ = C.c_void_p, C.c_int32, C.c_size_t
     SP = C.POINTER(FasaShape)
     lib.fasa_workspace_bytes.argtypes = [SP]; lib.fasa_workspace_bytes.restype = SZ
+    lib.fasa_workspace_init.argtypes = [SP, P, SZ, P]; lib.fasa_workspace_init.restype = C.c_int
     lib.fasa_validate_fc_idx.argtypes = [SP, P]; lib.fasa_validate_fc_idx.restype = C.c_int
     lib.fasa_pack_kcache.argtypes = [SP, P, P, P, I32, I32, P]; lib.fasa_pack_kcache.restype = C.c_int
     lib.fasa_score.argtypes = [SP, P, P, P, P, P]; lib.fasa_score.restype = C.c_int
@@ -98,7 +103,6 @@ def _ptr(x) -> Optional[int]:
 
 def _stream(stream) -> Optional[int]:
     if stream is None:
-        import torch
         return torch.cuda.current_stream().cuda_stream
     if hasattr(stream, "cuda_stream"):
         return stream.cuda_stream
@@ -112,6 +116,10 @@ def _check(status: int, where: str):
 
 def fasa_workspace_bytes(shape: FasaShape) -> int:
     return int(_lib.fasa_workspace_bytes(C.byref(shape)))
+
+
+def fasa_workspace_init(shape: FasaShape, ws, ws_bytes: int, stream=None) -> None:
+    _check(_lib.fasa_workspace_init(C.byref(shape), _ptr(ws), ws_bytes, _stream(stream)), "fasa_workspace_init")
 
 
 def fasa_validate_fc_idx(shape: FasaShape, fc_idx_host) -> None:

@@ -66,6 +66,7 @@ AttendPlan plan_attend(int rows, int count) {
   if (tps < 64) tps = 64;
   AttendPlan p;
   p.count = count;
+  if ((count + tps - 1) / tps > 256) tps = (((count + 255) / 256 + 63) / 64) * 64;  // <= 256 splits a row
   p.tok_per_split = (int)tps;
   p.n_splits = (int)((count + tps - 1) / tps);
   return p;
@@ -136,6 +137,18 @@ size_t fasa_workspace_bytes(const fasa_shape* shape) {
   return ws_layout(*shape).total;
 }
 
+int fasa_workspace_init(const fasa_shape* shape, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(shape, kNeedCtx | kNeedBudget);
+  if (rc != FASA_OK) return rc;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc != FASA_OK) return rc;
+  const WsLayout w = ws_layout(*shape);
+  char* base = (char*)ws;
+  FASA_HIP(launch_ws_clear(*shape, (uint32_t*)(base + w.hist_off), (RowCtl*)(base + w.ctl_off),
+                           (hipStream_t)stream));
+  return FASA_OK;
+}
+
 int fasa_validate_fc_idx(const fasa_shape* shape, const int32_t* fc_idx_host) {
   int rc = check_shape(shape, kNeedFc);
   if (rc != FASA_OK) return rc;
@@ -187,7 +200,6 @@ int fasa_topk(const fasa_shape* shape, const float* S, int32_t* T, void* ws, siz
   RowCtl* ctl = (RowCtl*)(base + w.ctl_off);
   uint2* cand = (uint2*)(base + w.cand_off);
   hipStream_t st = (hipStream_t)stream;
-  FASA_HIP(launch_prologue(*shape, hist, ctl, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, st));
   if (shape->budget < shape->n_ctx) FASA_HIP(launch_hist(*shape, S, hist, st));
   FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st));
   return FASA_OK;
@@ -207,8 +219,9 @@ static int attend_common(const fasa_shape* shape, bool dense, const void* q, con
   if (rc != FASA_OK) return rc;
   const WsLayout w = ws_layout(s);
   char* base = (char*)ws;
-  FASA_HIP(launch_attend(s, dense, q, K, V, T, O, (float*)(base + w.part_acc_off),
-                         (float*)(base + w.part_ml_off), (hipStream_t)stream));
+  FASA_HIP(launch_attend(s, dense, q, K, V, T, O, (RowCtl*)(base + w.ctl_off),
+                         (float*)(base + w.part_acc_off), (float*)(base + w.part_ml_off),
+                         (hipStream_t)stream));
   return FASA_OK;
 }
 
@@ -241,10 +254,10 @@ int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, v
   uint2* cand = (uint2*)(base + w.cand_off);
   hipStream_t st = (hipStream_t)stream;
   const bool select_all = shape->budget >= shape->n_ctx;
-  FASA_HIP(launch_prologue(*shape, hist, ctl, K, V, Kp, fc_idx, k_new, v_new, st));
+  if (k_new) FASA_HIP(launch_append(*shape, K, V, Kp, fc_idx, k_new, v_new, st));
   FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, select_all ? nullptr : hist, st));
   FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st));
-  FASA_HIP(launch_attend(*shape, false, q, K, V, T, O, (float*)(base + w.part_acc_off),
+  FASA_HIP(launch_attend(*shape, false, q, K, V, T, O, ctl, (float*)(base + w.part_acc_off),
                          (float*)(base + w.part_ml_off), st));
   return FASA_OK;
 }

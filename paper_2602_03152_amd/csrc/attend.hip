@@ -1,7 +1,7 @@
 // FAC (paper Sec. 4.2, eq. fac_output): exact softmax attention over the selected rows of K and V,
 // as split-K flash decoding: every workgroup owns a chunk of the row's index list, gathers the
 // K/V rows it names, keeps a running (max, sum, weighted V) per query head of the GQA group, and
-// a second small kernel merges the chunks.  The same kernel with the index list replaced by the
+// the workgroup that finishes a row last merges the row's chunks.  The same kernel with the index list replaced by the
 // identity is the full-KV baseline (paper Sec. 4.4).
 #include "fasa_device.h"
 #include "fasa_internal.h"
@@ -11,6 +11,7 @@ namespace fasa {
 constexpr int kAttU = 4;                  // rows in flight per 16-lane group and batch
 constexpr int kAttBatch = 4 * kAttU;      // rows per wave and batch
 constexpr float kNegBig = -1.0e30f;       // finite stand-in for -inf (keeps exp2 arguments finite)
+constexpr int kMaxSplitsLds = 256;        // most splits per row the merging workgroup can weight
 
 // 8 consecutive head dims of one cached row, widened to float32
 template <typename ET> struct Row8;
@@ -36,26 +37,114 @@ template <> struct Row8<float> {
 __device__ __forceinline__ float to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 __device__ __forceinline__ float to_f32(float v) { return v; }
 
-// grid = (n_splits, rows), 256 threads.  A wave is 4 groups of 16 lanes; a group reads one cached
-// row per load instruction (16 lanes x 16 bytes = one 256-byte bf16 row), lane c owning head dims
-// [8c, 8c+8) of K (for the logit) and of V (for the output).
+// Merges the split partials of one row into O.  Called by the row's last workgroup (all 256
+// threads).  The partials were published by other workgroups with agent-scope stores and are read
+// with agent-scope loads.  Pass 1: per query head the global maximum and the normalised weight of
+// every split, kept in LDS; pass 2: thread (half, dim) sums its half of the splits for all query
+// heads, up to 8 splits' loads in flight, then the two halves meet in LDS.
+template <int G>
+__device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
+                                            const float* __restrict__ part_ml,
+                                            float* __restrict__ O, int row, int b, int h, int Hq,
+                                            int n_splits, float* wsm /* [G][kMaxSplitsLds] */,
+                                            float* red /* [G] */, float* half_acc /* [G][D] */) {
+  constexpr int D = kHeadDim;
+  const int t = threadIdx.x;
+  const size_t rbase = (size_t)row * n_splits * G;
+  // one wave per query head (round-robin): max, then weights, then their sum
+  const int wave = t >> 6, lane = t & 63;
+  for (int g = wave; g < G; g += 4) {
+    float mv[kMaxSplitsLds / 64], lv[kMaxSplitsLds / 64];
+    float mx = kNegBig;
+#pragma unroll
+    for (int i = 0; i < kMaxSplitsLds / 64; ++i) {
+      const int s = lane + 64 * i;
+      mv[i] = kNegBig; lv[i] = 0.f;
+      if (s < n_splits) {
+        const size_t pi = (rbase + (size_t)s * G + g) * 2;
+        mv[i] = ld_agent(&part_ml[pi]);
+        lv[i] = ld_agent(&part_ml[pi + 1]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kMaxSplitsLds / 64; ++i) mx = fmaxf(mx, mv[i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxSplitsLds / 64; ++i) {
+      const int s = lane + 64 * i;
+      const float wgt = exp2f(mv[i] - mx);
+      if (s < n_splits) wsm[g * kMaxSplitsLds + s] = wgt;
+      sum = fmaf(lv[i], wgt, sum);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, kWave);
+    if (lane == 0) red[g] = 1.0f / sum;
+  }
+  __syncthreads();
+  const int dim = t & (D - 1), half = t >> 7;
+  float a[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) a[g] = 0.f;
+  const float* pa = part_acc + rbase * D + dim;
+  for (int s0 = half; s0 < n_splits; s0 += 16) {
+    float x[8][G];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = s0 + 2 * u;
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+        x[u][g] = (s < n_splits) ? ld_agent(&pa[((size_t)s * G + g) * D]) : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = s0 + 2 * u;
+      if (s < n_splits) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) a[g] = fmaf(x[u][g], wsm[g * kMaxSplitsLds + s], a[g]);
+      }
+    }
+  }
+  if (half == 1) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) half_acc[g * D + dim] = a[g];
+  }
+  __syncthreads();
+  if (half == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      O[((size_t)b * Hq + (size_t)h * G + g) * D + dim] = (a[g] + half_acc[g * D + dim]) * red[g];
+  }
+}
+
+// 1-D grid of rows * n_splits workgroups, 256 threads.  A wave is 4 groups of 16 lanes; a group
+// reads one cached row per load instruction (16 lanes x 16 bytes = one 256-byte bf16 row), lane c
+// owning head dims [8c, 8c+8) of K (for the logit) and of V (for the output).  The workgroup that
+// finishes a row last merges the row's partials into O.
 template <typename ET, int G, bool DENSE>
 __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
                                                      const ET* __restrict__ K,
                                                      const ET* __restrict__ V,
                                                      const int32_t* __restrict__ T,
+                                                     float* __restrict__ O,
+                                                     RowCtl* __restrict__ ctl,
                                                      float* __restrict__ part_acc,
-                                                     float* __restrict__ part_ml, int Hq, int Hkv,
-                                                     int count, int n_ctx, int tok_per_split,
-                                                     long long sb, long long sh, long long sn,
+                                                     float* __restrict__ part_ml, int rows,
+                                                     int n_splits, int Hq, int Hkv, int count,
+                                                     int n_ctx, int tok_per_split, long long sb,
+                                                     long long sh, long long sn,
                                                      float scale_log2e) {
   constexpr int D = kHeadDim;
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ float sm_acc[4][G][D];
+  __shared__ float wsm[G * kMaxSplitsLds];
+  __shared__ float red[G];
+  __shared__ uint32_t ticket;
 
-  const int row = blockIdx.y;
+  int row, split;
+  row_slice_of_block(rows, n_splits, row, split);
   const int b = row / Hkv, h = row % Hkv;
-  const int split = blockIdx.x;
   const int t = threadIdx.x;
   const int lane = t & 63, wave = t >> 6;
   const int r = lane >> 4, c = lane & 15;
@@ -111,16 +200,8 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
         float d = 0.f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) d = fmaf(qr[g][k], kf[k], d);
-        s[u][g] = d;
+        s[u][g] = row16_sum(d);   // all 16 lanes of the group end up with the logit
       }
-    }
-    // sum the 16 partial dot products of a group (all 16 lanes end up with the logit)
-#pragma unroll
-    for (int o = 1; o < 16; o <<= 1) {
-#pragma unroll
-      for (int u = 0; u < kAttU; ++u)
-#pragma unroll
-        for (int g = 0; g < G; ++g) s[u][g] += __shfl_xor(s[u][g], o, kWave);
     }
     float p[kAttU][G];
 #pragma unroll
@@ -180,7 +261,7 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
   __syncthreads();
 
   // merge the 4 waves; one (query head, head dim) per thread and pass
-  const size_t pbase = ((size_t)row * gridDim.x + split) * G;
+  const size_t pbase = ((size_t)row * n_splits + split) * G;
   for (int i = t; i < G * D; i += 256) {
     const int g = i / D, dim = i % D;
     float mn = sm_m[0][g];
@@ -193,86 +274,76 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
       ls = fmaf(sm_l[w][g], sc, ls);
       a = fmaf(sm_acc[w][g][dim], sc, a);
     }
-    part_acc[(pbase + g) * D + dim] = a;
-    if (dim == 0) {
-      part_ml[(pbase + g) * 2] = mn;
-      part_ml[(pbase + g) * 2 + 1] = ls;
+    if (n_splits == 1) {
+      O[((size_t)b * Hq + (size_t)h * G + g) * D + dim] = a / ls;   // nothing to merge
+    } else {
+      // read by the row's last workgroup: published with agent-scope stores
+      st_agent(&part_acc[(pbase + g) * D + dim], a);
+      if (dim == 0) {
+        st_agent(&part_ml[(pbase + g) * 2], mn);
+        st_agent(&part_ml[(pbase + g) * 2 + 1], ls);
+      }
     }
   }
-}
+  if (n_splits == 1) return;
 
-// grid = batch * Hq, 128 threads (one head dim each): O = sum_s acc_s 2^(m_s - m*) / sum_s l_s 2^(m_s - m*)
-__global__ __launch_bounds__(128) void combine_kernel(const float* __restrict__ part_acc,
-                                                      const float* __restrict__ part_ml,
-                                                      float* __restrict__ O, int Hq, int Hkv,
-                                                      int n_splits) {
-  constexpr int D = kHeadDim;
-  const int bh = blockIdx.x;
-  const int b = bh / Hq, hq = bh % Hq;
-  const int G = Hq / Hkv;
-  const int row = b * Hkv + hq / G, g = hq % G;
-  const int dim = threadIdx.x;
-  float mn = kNegBig;
-  for (int s = 0; s < n_splits; ++s)
-    mn = fmaxf(mn, part_ml[(((size_t)row * n_splits + s) * G + g) * 2]);
-  float ls = 0.f, a = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const size_t pi = ((size_t)row * n_splits + s) * G + g;
-    const float sc = exp2f(part_ml[pi * 2] - mn);
-    ls = fmaf(part_ml[pi * 2 + 1], sc, ls);
-    a = fmaf(part_acc[pi * D + dim], sc, a);
-  }
-  O[(size_t)bh * D + dim] = a / ls;
+  // ---- the row's last workgroup merges the splits ----
+  publish_barrier();
+  if (t == 0) ticket = atomicAdd(&ctl[row].done_att, 1u);
+  __syncthreads();
+  if (ticket != (uint32_t)n_splits - 1u) return;
+  if (t == 0) ctl[row].done_att = 0;   // clean for the next call
+  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, wsm, red, &sm_acc[0][0][0]);
 }
 
 template <typename ET, int G>
 static hipError_t launch_attend_g(const fasa_shape& s, bool dense, const AttendPlan& p,
                                   const void* q, const void* K, const void* V, const int32_t* T,
-                                  float* part_acc, float* part_ml, hipStream_t st) {
+                                  float* O, RowCtl* ctl, float* part_acc, float* part_ml,
+                                  hipStream_t st) {
   const int rows = s.batch * s.n_kv_heads;
-  dim3 grid(p.n_splits, rows), block(256);
+  dim3 grid(rows * p.n_splits), block(256);
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)s.head_dim);
   if (dense)
     return launch("fasa_dense_attend", attend_kernel<ET, G, true>, grid, block, st, (const ET*)q,
-                  (const ET*)K, (const ET*)V, T, part_acc, part_ml, s.n_q_heads, s.n_kv_heads,
-                  p.count, s.n_ctx, p.tok_per_split, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                  (long long)s.kv_stride_n, scale_log2e);
+                  (const ET*)K, (const ET*)V, T, O, ctl, part_acc, part_ml, rows, p.n_splits,
+                  s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx, p.tok_per_split,
+                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n,
+                  scale_log2e);
   return launch("fasa_sparse_attend", attend_kernel<ET, G, false>, grid, block, st, (const ET*)q,
-                (const ET*)K, (const ET*)V, T, part_acc, part_ml, s.n_q_heads, s.n_kv_heads,
-                p.count, s.n_ctx, p.tok_per_split, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                (long long)s.kv_stride_n, scale_log2e);
+                (const ET*)K, (const ET*)V, T, O, ctl, part_acc, part_ml, rows, p.n_splits,
+                s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx, p.tok_per_split,
+                (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n,
+                scale_log2e);
 }
 
 template <typename ET>
 static hipError_t launch_attend_t(const fasa_shape& s, bool dense, const AttendPlan& p,
                                   const void* q, const void* K, const void* V, const int32_t* T,
-                                  float* part_acc, float* part_ml, hipStream_t st) {
+                                  float* O, RowCtl* ctl, float* part_acc, float* part_ml,
+                                  hipStream_t st) {
   switch (s.n_q_heads / s.n_kv_heads) {
-    case 1: return launch_attend_g<ET, 1>(s, dense, p, q, K, V, T, part_acc, part_ml, st);
-    case 2: return launch_attend_g<ET, 2>(s, dense, p, q, K, V, T, part_acc, part_ml, st);
-    case 3: return launch_attend_g<ET, 3>(s, dense, p, q, K, V, T, part_acc, part_ml, st);
-    case 4: return launch_attend_g<ET, 4>(s, dense, p, q, K, V, T, part_acc, part_ml, st);
-    case 5: return launch_attend_g<ET, 5>(s, dense, p, q, K, V, T, part_acc, part_ml, st);
-    case 6: return launch_attend_g<ET, 6>(s, dense, p, q, K, V, T, part_acc, part_ml, st);
-    case 7: return launch_attend_g<ET, 7>(s, dense, p, q, K, V, T, part_acc, part_ml, st);
-    case 8: return launch_attend_g<ET, 8>(s, dense, p, q, K, V, T, part_acc, part_ml, st);
+    case 1: return launch_attend_g<ET, 1>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
+    case 2: return launch_attend_g<ET, 2>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
+    case 3: return launch_attend_g<ET, 3>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
+    case 4: return launch_attend_g<ET, 4>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
+    case 5: return launch_attend_g<ET, 5>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
+    case 6: return launch_attend_g<ET, 6>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
+    case 7: return launch_attend_g<ET, 7>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
+    case 8: return launch_attend_g<ET, 8>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
     default: return hipErrorInvalidValue;
   }
 }
 
 hipError_t launch_attend(const fasa_shape& s, bool dense, const void* q, const void* K,
-                         const void* V, const int32_t* T, float* O, float* part_acc, float* part_ml,
-                         hipStream_t st) {
+                         const void* V, const int32_t* T, float* O, RowCtl* ctl, float* part_acc,
+                         float* part_ml, hipStream_t st) {
   const int rows = s.batch * s.n_kv_heads;
   const int count = dense ? s.n_ctx : (s.budget < s.n_ctx ? s.budget : s.n_ctx);
   const AttendPlan p = plan_attend(rows, count);
-  hipError_t e = s.dtype == FASA_BF16
-                     ? launch_attend_t<uint16_t>(s, dense, p, q, K, V, T, part_acc, part_ml, st)
-                     : launch_attend_t<float>(s, dense, p, q, K, V, T, part_acc, part_ml, st);
-  if (e != hipSuccess) return e;
-  return launch("fasa_combine", combine_kernel, dim3(s.batch * s.n_q_heads), dim3(128), st,
-                (const float*)part_acc, (const float*)part_ml, O, s.n_q_heads, s.n_kv_heads,
-                p.n_splits);
+  return s.dtype == FASA_BF16
+             ? launch_attend_t<uint16_t>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st)
+             : launch_attend_t<float>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
 }
 
 }  // namespace fasa

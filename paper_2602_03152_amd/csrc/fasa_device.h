@@ -60,4 +60,94 @@ __device__ __forceinline__ uint32_t block256_suffix_sum(uint32_t v, uint32_t* wt
   return s + add;
 }
 
+// Exclusive prefix over a 256-thread block of two counters at once; also returns the block totals.
+// `ws` is an 8-entry LDS scratch.  Contains two block barriers.
+__device__ __forceinline__ void block256_prefix2(uint32_t a, uint32_t b, uint32_t* ws, uint32_t& pa,
+                                                 uint32_t& pb, uint32_t& ta, uint32_t& tb) {
+  const int wave = (int)(threadIdx.x >> 6);
+  const uint32_t ia = wave_prefix_sum(a), ib = wave_prefix_sum(b);
+  __syncthreads();
+  if (lane_id() == kWave - 1) { ws[wave] = ia; ws[4 + wave] = ib; }
+  __syncthreads();
+  uint32_t oa = 0, ob = 0;
+  ta = 0; tb = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (w < wave) { oa += ws[w]; ob += ws[4 + w]; }
+    ta += ws[w]; tb += ws[4 + w];
+  }
+  pa = oa + ia - a;
+  pb = ob + ib - b;
+}
+
+// Maps the linear workgroup id of a 1-D grid of rows * nslices workgroups to (row, slice).
+// Workgroups are handed to the 8 XCDs round-robin, so when the row count is a multiple of 8 the
+// mapping keeps every workgroup of a row on one XCD: the row's counters, histogram and score
+// slice then live in that XCD's L2 and its atomics do not bounce between dies.
+__device__ __forceinline__ void row_slice_of_block(int rows, int nslices, int& row, int& slice) {
+  const unsigned id = blockIdx.x;
+  if ((rows & 7) == 0) {
+    const unsigned xcd = id & 7u, k = id >> 3;
+    slice = (int)(k % (unsigned)nslices);
+    row = (int)(k / (unsigned)nslices) * 8 + (int)xcd;
+  } else {
+    row = (int)(id / (unsigned)nslices);
+    slice = (int)(id % (unsigned)nslices);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Publishing small results to another workgroup of the same kernel without a device-scope fence.
+// A release fence at agent scope writes back the whole L2 of the XCD (hundreds of ns, serialised
+// per die), far too much for kernels of a few microseconds.  Instead the producer writes the
+// shared words with agent-scope (write-through) stores, waits until they are acknowledged, and
+// only then bumps a ticket; the consumer reads the words with agent-scope loads, which are served
+// from the coherence point and never from a stale line.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void st_agent(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(int32_t* p, int32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(uint2* p, uint2 v) {
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p),
+                     ((unsigned long long)v.y << 32) | v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint2 ld_agent(const uint2* p) {
+  const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
+}
+// All of this workgroup's earlier stores are acknowledged; then a block barrier.  After it one
+// thread may bump the ticket that tells another workgroup the data is there.
+__device__ __forceinline__ void publish_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);   // vmcnt = expcnt = lgkmcnt = 0
+  __syncthreads();
+}
+
+// DPP lane exchanges inside a row of 16 lanes (no LDS traffic)
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+// sum over the 16 lanes of a DPP row; every lane of the row gets the same bits
+__device__ __forceinline__ float row16_sum(float x) {
+  x += dpp_mov<0xB1>(x);   // quad_perm [1,0,3,2]
+  x += dpp_mov<0x4E>(x);   // quad_perm [2,3,0,1]
+  x += dpp_mov<0x141>(x);  // row_half_mirror
+  x += dpp_mov<0x140>(x);  // row_mirror
+  return x;
+}
+
 }  // namespace fasa

@@ -22,13 +22,16 @@ constexpr int kKeyLowBits = 32 - kHistBits;
 constexpr int kHeadDim = 128;
 constexpr int kMaxGroup = 8;
 
-// per-(b,h) row counters of the selection stage
+// Per-(b,h) row counters, one 128-byte line per row so that rows served by different XCDs never
+// share a line.  All zero between calls: the workgroup that finishes a row resets what it used.
 struct RowCtl {
-  uint32_t n_sel;   // winners written so far (tokens in bins above the threshold bin)
-  uint32_t n_cand;  // candidates collected from the threshold bin
-  uint32_t done;    // blocks of this row that finished their slice
-  uint32_t pad;
+  uint32_t n_sel;     // winners written so far (tokens in bins above the threshold bin)
+  uint32_t n_cand;    // candidates collected from the threshold bin
+  uint32_t done_sel;  // selection workgroups of this row that finished their slice
+  uint32_t done_att;  // attention workgroups of this row that wrote their partial
+  uint32_t pad[28];
 };
+static_assert(sizeof(RowCtl) == 128, "one line per row");
 
 // Workspace carve-up (all offsets 256-byte aligned).
 struct WsLayout {
@@ -82,15 +85,16 @@ hipError_t launch_pack(const fasa_shape& s, const void* K, const int32_t* fc_idx
 // hist == nullptr: scores only
 hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
                         float* S, uint32_t* hist, hipStream_t st);
-// clears histogram + row counters; with k_new also appends the new K/V row and its packed FCs
-hipError_t launch_prologue(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, void* K, void* V,
-                           void* Kp, const int32_t* fc_idx, const void* k_new, const void* v_new,
-                           hipStream_t st);
+// zeroes the histogram and the row counters (workspace initialisation)
+hipError_t launch_ws_clear(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, hipStream_t st);
+// appends the new K/V row (position n_ctx - 1) and its packed FCs
+hipError_t launch_append(const fasa_shape& s, void* K, void* V, void* Kp, const int32_t* fc_idx,
+                         const void* k_new, const void* v_new, hipStream_t st);
 hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st);
 hipError_t launch_select(const fasa_shape& s, const float* S, const uint32_t* hist, RowCtl* ctl,
                          uint2* cand, int32_t* T, hipStream_t st);
 hipError_t launch_attend(const fasa_shape& s, bool dense, const void* q, const void* K,
-                         const void* V, const int32_t* T, float* O, float* part_acc, float* part_ml,
-                         hipStream_t st);
+                         const void* V, const int32_t* T, float* O, RowCtl* ctl, float* part_acc,
+                         float* part_ml, hipStream_t st);
 
 }  // namespace fasa

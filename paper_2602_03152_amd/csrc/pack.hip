@@ -1,6 +1,6 @@
 // Dominant-key cache maintenance: the FC-major packed copy Kp of the dominant K dims
-// (paper Alg. 2, Split + UpdateCache of k^dom), and the per-step prologue that clears the
-// selection counters and appends a freshly decoded K/V row.
+// (paper Alg. 2, Split + UpdateCache of k^dom), and the per-step append of a freshly decoded
+// K/V row.
 #include "fasa_device.h"
 #include "fasa_internal.h"
 
@@ -53,32 +53,26 @@ __global__ __launch_bounds__(256) void pack_kernel(const ET* __restrict__ K,
   }
 }
 
-// grid = (kHistBins / 1024, rows).  Every block clears 1024 histogram bins of its row; block x == 0
-// also clears the row counters and, when k_new is given, writes the new token (position n_ctx - 1)
-// into K, V and the packed planes.
+// grid = rows, 256 threads: writes the freshly decoded token (position n_ctx - 1) into K, V and
+// the packed planes (paper Alg. 2: the new key joins the dominant cache before scoring).
 template <typename ET>
-__global__ __launch_bounds__(256) void prologue_kernel(uint32_t* __restrict__ hist,
-                                                       RowCtl* __restrict__ ctl, ET* __restrict__ K,
-                                                       ET* __restrict__ V, ET* __restrict__ Kp,
-                                                       const int32_t* __restrict__ fc_idx,
-                                                       const ET* __restrict__ k_new,
-                                                       const ET* __restrict__ v_new, int Hkv, int F,
-                                                       int n_cap, int n_ctx, long long sb,
-                                                       long long sh, long long sn) {
+__global__ __launch_bounds__(256) void append_kernel(ET* __restrict__ K, ET* __restrict__ V,
+                                                     ET* __restrict__ Kp,
+                                                     const int32_t* __restrict__ fc_idx,
+                                                     const ET* __restrict__ k_new,
+                                                     const ET* __restrict__ v_new, int Hkv, int F,
+                                                     int n_cap, int n_ctx, long long sb,
+                                                     long long sh, long long sn) {
   constexpr int D = kHeadDim;
-  const int row = blockIdx.y;
+  const int row = blockIdx.x;
   const int t = threadIdx.x;
-  reinterpret_cast<uint4*>(hist + (size_t)row * kHistBins + blockIdx.x * 1024)[t] = make_uint4(0, 0, 0, 0);
-  if (blockIdx.x != 0) return;
-  if (t == 0) ctl[row] = RowCtl{0u, 0u, 0u, 0u};
-  if (k_new == nullptr) return;
   const int b = row / Hkv, h = row % Hkv;
   const int n = n_ctx - 1;
   const ET* ks = k_new + (size_t)row * D;
   const ET* vs = v_new + (size_t)row * D;
   if (t < D) {
     K[b * sb + h * sh + (long long)n * sn + t] = ks[t];
-  } else if (t < 2 * D) {
+  } else {
     V[b * sb + h * sh + (long long)n * sn + (t - D)] = vs[t - D];
   }
   if (t < F) {
@@ -102,20 +96,19 @@ hipError_t launch_pack(const fasa_shape& s, const void* K, const int32_t* fc_idx
                 (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
 }
 
-hipError_t launch_prologue(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, void* K, void* V,
-                           void* Kp, const int32_t* fc_idx, const void* k_new, const void* v_new,
-                           hipStream_t st) {
+hipError_t launch_append(const fasa_shape& s, void* K, void* V, void* Kp, const int32_t* fc_idx,
+                         const void* k_new, const void* v_new, hipStream_t st) {
   const int rows = s.batch * s.n_kv_heads;
-  dim3 grid(kHistBins / 1024, rows), block(256);
+  dim3 grid(rows), block(256);
   if (s.dtype == FASA_BF16)
-    return launch("fasa_prologue", prologue_kernel<uint16_t>, grid, block, st, hist, ctl,
-                  (uint16_t*)K, (uint16_t*)V, (uint16_t*)Kp, fc_idx, (const uint16_t*)k_new,
+    return launch("fasa_append", append_kernel<uint16_t>, grid, block, st, (uint16_t*)K,
+                  (uint16_t*)V, (uint16_t*)Kp, fc_idx, (const uint16_t*)k_new,
                   (const uint16_t*)v_new, s.n_kv_heads, s.n_fc, s.n_cap, s.n_ctx,
                   (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
-  return launch("fasa_prologue", prologue_kernel<float>, grid, block, st, hist, ctl, (float*)K,
-                (float*)V, (float*)Kp, fc_idx, (const float*)k_new, (const float*)v_new,
-                s.n_kv_heads, s.n_fc, s.n_cap, s.n_ctx, (long long)s.kv_stride_b,
-                (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+  return launch("fasa_append", append_kernel<float>, grid, block, st, (float*)K, (float*)V,
+                (float*)Kp, fc_idx, (const float*)k_new, (const float*)v_new, s.n_kv_heads, s.n_fc,
+                s.n_cap, s.n_ctx, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
+                (long long)s.kv_stride_n);
 }
 
 }  // namespace fasa

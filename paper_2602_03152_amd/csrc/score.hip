@@ -27,24 +27,42 @@ __device__ __forceinline__ void fma_pairs<float>(const uint4& w, float qlo, floa
   acc[1] = fmaf(qhi, __uint_as_float(w.w), fmaf(qlo, __uint_as_float(w.z), acc[1]));
 }
 
-// grid = (ceil(N / (256 * TPT)), rows); one 16-byte load per thread per FC plane: a wave reads
-// 1 KiB contiguous from each of the F planes, F independent loads in flight per lane.
+constexpr int kScoreFB = 16;  // FC planes in flight per thread
+
+// 1-D grid of rows * nslices workgroups, nslices = ceil(N / (256 * TPT)).  One 16-byte load per
+// thread per FC plane: a wave reads 1 KiB contiguous from each plane, up to 16 independent loads in
+// flight per lane.  The loads are issued before anything else; the query gather and the LDS
+// clearing run under their latency.
 template <typename ET, bool HIST>
 __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
                                                     const ET* __restrict__ Kp,
                                                     const int32_t* __restrict__ fc_idx,
                                                     float* __restrict__ S,
-                                                    uint32_t* __restrict__ hist, int Hq, int Hkv,
-                                                    int F, int N, int n_cap) {
+                                                    uint32_t* __restrict__ hist, int rows,
+                                                    int nslices, int Hq, int Hkv, int F, int N,
+                                                    int n_cap) {
   constexpr int D = kHeadDim;
   constexpr int TPT = ScoreTraits<ET>::TPT;
   __shared__ float2 qs[D / 2];
   __shared__ uint32_t lh[HIST ? kHistBins : 1];
 
-  const int row = blockIdx.y;
+  int row, slice;
+  row_slice_of_block(rows, nslices, row, slice);
   const int b = row / Hkv, h = row % Hkv;
   const int G = Hq / Hkv;
   const int t = threadIdx.x;
+  const int n0 = (slice * 256 + t) * TPT;
+  const bool active = n0 < N;
+  const ET* p = Kp + ((size_t)row * F * n_cap + (active ? n0 : 0)) * 2;
+  const size_t plane = (size_t)n_cap * 2;
+
+  uint4 w[kScoreFB];
+  int nf = min(F, kScoreFB);
+  if (active) {
+#pragma unroll
+    for (int u = 0; u < kScoreFB; ++u)
+      if (u < nf) w[u] = *reinterpret_cast<const uint4*>(p + (size_t)u * plane);
+  }
 
   if (t < F) {
     // group-summed dominant query components: sum_g (q_g . k) = (sum_g q_g) . k
@@ -67,28 +85,24 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
   }
   __syncthreads();
 
-  const int n0 = (blockIdx.x * 256 + t) * TPT;
-  if (n0 < N) {
-    const ET* p = Kp + ((size_t)row * F * n_cap + n0) * 2;
-    const size_t plane = (size_t)n_cap * 2;
+  if (active) {
     float acc[TPT];
 #pragma unroll
     for (int k = 0; k < TPT; ++k) acc[k] = 0.f;
-    int f = 0;
-    for (; f + 8 <= F; f += 8) {
-      uint4 w[8];
+    for (int f0 = 0;;) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) w[u] = *reinterpret_cast<const uint4*>(p + (size_t)(f + u) * plane);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const float2 qf = qs[f + u];
-        fma_pairs<ET>(w[u], qf.x, qf.y, acc);
+      for (int u = 0; u < kScoreFB; ++u) {
+        if (u < nf) {
+          const float2 qf = qs[f0 + u];
+          fma_pairs<ET>(w[u], qf.x, qf.y, acc);
+        }
       }
-    }
-    for (; f < F; ++f) {
-      const uint4 w = *reinterpret_cast<const uint4*>(p + (size_t)f * plane);
-      const float2 qf = qs[f];
-      fma_pairs<ET>(w, qf.x, qf.y, acc);
+      f0 += kScoreFB;
+      if (f0 >= F) break;
+      nf = min(F - f0, kScoreFB);
+#pragma unroll
+      for (int u = 0; u < kScoreFB; ++u)
+        if (u < nf) w[u] = *reinterpret_cast<const uint4*>(p + (size_t)(f0 + u) * plane);
     }
     float* out = S + (size_t)row * n_cap + n0;
     if (n0 + TPT <= N) {
@@ -146,28 +160,25 @@ __global__ __launch_bounds__(256) void hist_kernel(const float* __restrict__ S,
   }
 }
 
+template <typename ET>
+static hipError_t launch_score_t(const fasa_shape& s, const void* q, const void* Kp,
+                                 const int32_t* fc_idx, float* S, uint32_t* hist, hipStream_t st) {
+  const int rows = s.batch * s.n_kv_heads;
+  const int per_block = 256 * ScoreTraits<ET>::TPT;
+  const int nslices = (s.n_ctx + per_block - 1) / per_block;
+  dim3 grid(rows * nslices), block(256);
+  if (hist)
+    return launch("fasa_score_hist", score_kernel<ET, true>, grid, block, st, (const ET*)q,
+                  (const ET*)Kp, fc_idx, S, hist, rows, nslices, s.n_q_heads, s.n_kv_heads, s.n_fc,
+                  s.n_ctx, s.n_cap);
+  return launch("fasa_score", score_kernel<ET, false>, grid, block, st, (const ET*)q, (const ET*)Kp,
+                fc_idx, S, hist, rows, nslices, s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap);
+}
+
 hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
                         float* S, uint32_t* hist, hipStream_t st) {
-  const int rows = s.batch * s.n_kv_heads;
-  dim3 block(256);
-  if (s.dtype == FASA_BF16) {
-    dim3 grid((s.n_ctx + 1023) / 1024, rows);
-    if (hist)
-      return launch("fasa_score_hist", score_kernel<uint16_t, true>, grid, block, st,
-                    (const uint16_t*)q, (const uint16_t*)Kp, fc_idx, S, hist, s.n_q_heads,
-                    s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap);
-    return launch("fasa_score", score_kernel<uint16_t, false>, grid, block, st, (const uint16_t*)q,
-                  (const uint16_t*)Kp, fc_idx, S, hist, s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx,
-                  s.n_cap);
-  }
-  dim3 grid((s.n_ctx + 511) / 512, rows);
-  if (hist)
-    return launch("fasa_score_hist", score_kernel<float, true>, grid, block, st, (const float*)q,
-                  (const float*)Kp, fc_idx, S, hist, s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx,
-                  s.n_cap);
-  return launch("fasa_score", score_kernel<float, false>, grid, block, st, (const float*)q,
-                (const float*)Kp, fc_idx, S, hist, s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx,
-                s.n_cap);
+  return s.dtype == FASA_BF16 ? launch_score_t<uint16_t>(s, q, Kp, fc_idx, S, hist, st)
+                              : launch_score_t<float>(s, q, Kp, fc_idx, S, hist, st);
 }
 
 hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st) {

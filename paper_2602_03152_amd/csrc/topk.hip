@@ -5,24 +5,29 @@
 //   level 0  the per-row histogram of the top 12 key bits (built by the scoring kernel or by
 //            hist_kernel) fixes the threshold bin: bins above it hold fewer than B tokens, bins
 //            from it upwards at least B;
-//   filter   many workgroups per row stream S once; tokens above the threshold bin are winners
-//            and go straight to T, tokens inside it are appended to a candidate list;
+//   filter   several workgroups per row stream S once; tokens above the threshold bin are winners
+//            and go straight to T, tokens inside it are appended to a candidate list; positions
+//            come from a block-wide prefix sum plus ONE atomic per workgroup and counter;
 //   final    the last workgroup of the row to finish resolves the candidates exactly: radix
 //            select, 8 bits a pass, over the 56-bit composite (low 20 key bits : ~index), which
-//            is unique per token, so exactly B - |winners| candidates come out.
+//            is unique per token, so exactly B - |winners| candidates come out.  It then zeroes
+//            the row's histogram and counters, which leaves the workspace clean for the next call.
 #include "fasa_device.h"
 #include "fasa_internal.h"
 
 namespace fasa {
 
-constexpr int kSelTokPerBlock = 2048;  // slice of a row filtered by one workgroup
-constexpr int kCandLds = 4096;         // candidates resolved out of LDS; more spill to global reads
+constexpr int kSelTokPerBlock = 2048;           // slice of a row filtered by one workgroup
+constexpr int kSelPerThread = kSelTokPerBlock / 256;
+constexpr int kCandLds = 4096;                  // candidates resolved out of LDS; more: global reads
 
 __device__ __forceinline__ unsigned long long cand_composite(uint2 c) {
   return ((unsigned long long)(c.x & ((1u << kKeyLowBits) - 1u)) << 32) | (unsigned long long)(~c.y);
 }
 
 // Exact selection of the `need` largest composites among cand[0..n).  Whole block participates.
+// SHARED_SRC: the list lives in global memory and was written by other workgroups.
+template <bool SHARED_SRC>
 __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* out,
                                    uint32_t* dh /*256*/, uint32_t* wtot /*4*/,
                                    uint32_t* bc /*4: digit, need, count, out counter*/) {
@@ -36,7 +41,7 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
       dh[t] = 0;
       __syncthreads();
       for (int i = t; i < n; i += 256) {
-        const unsigned long long c = cand_composite(cand[i]);
+        const unsigned long long c = cand_composite(SHARED_SRC ? ld_agent(&cand[i]) : cand[i]);
         if ((c >> (shift + 8)) == prefix) atomicAdd(&dh[(uint32_t)(c >> shift) & 0xFFu], 1u);
       }
       __syncthreads();
@@ -59,7 +64,7 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
     shift = 56;  // take all: (c >> 56) == 0 >= 0
   }
   for (int i = t; i < n; i += 256) {
-    const uint2 c = cand[i];
+    const uint2 c = SHARED_SRC ? ld_agent(&cand[i]) : cand[i];
     if ((cand_composite(c) >> shift) >= prefix) {
       const uint32_t pos = atomicAdd(&bc[3], 1u);
       if (pos < out_cap) out[pos] = (int32_t)c.y;
@@ -67,33 +72,49 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
   }
 }
 
-// grid = (ceil(N / kSelTokPerBlock), rows)
+// 1-D grid of rows * nslices workgroups, nslices = ceil(N / kSelTokPerBlock)
 __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S,
-                                                     const uint32_t* __restrict__ hist,
+                                                     uint32_t* __restrict__ hist,
                                                      RowCtl* __restrict__ ctl,
                                                      uint2* __restrict__ cand,
-                                                     int32_t* __restrict__ T, int N, int n_cap,
-                                                     int bsel) {
-  __shared__ uint32_t wtot[4];
+                                                     int32_t* __restrict__ T, int rows, int nslices,
+                                                     int N, int n_cap, int bsel) {
+  __shared__ uint32_t wtot[8];
   __shared__ uint32_t bc[4];
   __shared__ uint32_t thr[2];  // threshold bin, tokens above it
   __shared__ uint32_t dh[256];
   __shared__ uint2 lc[kCandLds];
 
-  const int row = blockIdx.y;
+  int row, slice;
+  row_slice_of_block(rows, nslices, row, slice);
   const int t = threadIdx.x;
-  const int lane = lane_id();
-  const uint32_t* gh = hist + (size_t)row * kHistBins;
+  const float* s = S + (size_t)row * n_cap;
+  const int base = slice * kSelTokPerBlock;
+
+  // ---- this workgroup's scores: loads go out first, the histogram work hides their latency ----
+  float v[kSelPerThread];
+#pragma unroll
+  for (int it = 0; it < kSelPerThread / 4; ++it) {
+    const int n0 = base + (it * 256 + t) * 4;
+    if (n0 + 4 <= N) {
+      const float4 x = *reinterpret_cast<const float4*>(s + n0);
+      v[4 * it] = x.x; v[4 * it + 1] = x.y; v[4 * it + 2] = x.z; v[4 * it + 3] = x.w;
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[4 * it + k] = (n0 + k < N) ? s[n0 + k] : 0.f;
+    }
+  }
 
   // ---- threshold bin from the coarse histogram (every workgroup of the row redoes this) ----
+  uint32_t* gh = hist + (size_t)row * kHistBins;
   if (t == 0) { thr[0] = 0; thr[1] = 0; }
   {
     uint32_t hb[16];
     const uint4* hp = reinterpret_cast<const uint4*>(gh + t * 16);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const uint4 v = hp[j];
-      hb[4 * j] = v.x; hb[4 * j + 1] = v.y; hb[4 * j + 2] = v.z; hb[4 * j + 3] = v.w;
+      const uint4 x = hp[j];
+      hb[4 * j] = x.x; hb[4 * j + 1] = x.y; hb[4 * j + 2] = x.z; hb[4 * j + 3] = x.w;
     }
     uint32_t mine = 0;
 #pragma unroll
@@ -115,72 +136,64 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   const uint32_t tbin = thr[0];
   const uint32_t n_above = thr[1];
 
-  // ---- filter this workgroup's slice ----
-  const float* s = S + (size_t)row * n_cap;
+  // ---- classify, then one position range per workgroup and counter ----
+  uint32_t key[kSelPerThread];
+  uint32_t win = 0, cnd = 0;  // bit k set: this thread's k-th token is a winner / candidate
+#pragma unroll
+  for (int k = 0; k < kSelPerThread; ++k) {
+    const int n = base + ((k >> 2) * 256 + t) * 4 + (k & 3);
+    key[k] = score_key(v[k]);
+    const uint32_t bin = key[k] >> kKeyLowBits;
+    const bool ok = n < N;
+    win |= (ok && bin > tbin) ? (1u << k) : 0u;
+    cnd |= (ok && bin == tbin) ? (1u << k) : 0u;
+  }
+  uint32_t pw, pc, tw, tc;
+  block256_prefix2(__popc(win), __popc(cnd), wtot, pw, pc, tw, tc);
+  if (t == 0) {
+    bc[0] = tw ? atomicAdd(&ctl[row].n_sel, tw) : 0u;
+    bc[1] = tc ? atomicAdd(&ctl[row].n_cand, tc) : 0u;
+  }
+  __syncthreads();
+  uint32_t bw = bc[0] + pw, bcand = bc[1] + pc;
   int32_t* trow = T + (size_t)row * bsel;
   uint2* crow = cand + (size_t)row * n_cap;
-  const int base = blockIdx.x * kSelTokPerBlock;
-#pragma unroll 1
-  for (int it = 0; it < kSelTokPerBlock / 1024; ++it) {
-    const int n0 = base + (it * 256 + t) * 4;
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
-    if (n0 + 4 <= N) {
-      const float4 x = *reinterpret_cast<const float4*>(s + n0);
-      v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
-    } else {
-      for (int k = 0; k < 4; ++k)
-        if (n0 + k < N) v[k] = s[n0 + k];
-    }
-    uint32_t key[4];
-    uint32_t win = 0, cnd = 0;  // bit k set: token n0 + k is a winner / candidate
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      key[k] = score_key(v[k]);
-      const uint32_t bin = key[k] >> kKeyLowBits;
-      const bool ok = n0 + k < N;
-      win |= (ok && bin > tbin) ? (1u << k) : 0u;
-      cnd |= (ok && bin == tbin) ? (1u << k) : 0u;
-    }
-    const uint32_t nw = __popc(win), nc = __popc(cnd);
-    const uint32_t pw = wave_prefix_sum(nw), pc = wave_prefix_sum(nc);
-    const uint32_t tw = __shfl(pw, kWave - 1, kWave), tc = __shfl(pc, kWave - 1, kWave);
-    uint32_t bw = 0, bcand = 0;
-    if (lane == 0) {
-      if (tw) bw = atomicAdd(&ctl[row].n_sel, tw);
-      if (tc) bcand = atomicAdd(&ctl[row].n_cand, tc);
-    }
-    bw = __shfl(bw, 0, kWave) + pw - nw;
-    bcand = __shfl(bcand, 0, kWave) + pc - nc;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      // the bounds hold by construction of the histogram; they are re-checked so that a
-      // histogram that does not match S can never turn into an out-of-range store
-      if ((win & (1u << k)) && bw < (uint32_t)bsel) trow[bw++] = n0 + k;
-      if ((cnd & (1u << k)) && bcand < (uint32_t)n_cap) crow[bcand++] = make_uint2(key[k], (uint32_t)(n0 + k));
-    }
+  for (int k = 0; k < kSelPerThread; ++k) {
+    const int n = base + ((k >> 2) * 256 + t) * 4 + (k & 3);
+    // the bounds hold by construction of the histogram; they are re-checked so that a
+    // histogram that does not match S can never turn into an out-of-range store
+    if ((win & (1u << k)) && bw < (uint32_t)bsel) trow[bw++] = n;
+    // candidates are read by the row's last workgroup: published with agent-scope stores
+    if ((cnd & (1u << k)) && bcand < (uint32_t)n_cap) st_agent(&crow[bcand++], make_uint2(key[k], (uint32_t)n));
   }
 
   // ---- last workgroup of the row resolves the threshold bin ----
-  __threadfence();
+  publish_barrier();
+  if (t == 0) bc[2] = atomicAdd(&ctl[row].done_sel, 1u);
   __syncthreads();
-  if (t == 0) bc[0] = atomicAdd(&ctl[row].done, 1u);
-  __syncthreads();
-  const bool last = bc[0] == gridDim.x - 1;
+  const bool last = bc[2] == (uint32_t)nslices - 1u;
   __syncthreads();
   if (!last) return;
-  __threadfence();
-  int n_cand = (int)__hip_atomic_load(&ctl[row].n_cand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  int n_cand = (int)ld_agent(&ctl[row].n_cand);
   n_cand = min(n_cand, n_cap);
   const int need = max(0, min(bsel - (int)n_above, n_cand));
   if (t == 0) bc[3] = 0;
-  const uint2* src = crow;
-  if (n_cand <= kCandLds) {
-    for (int i = t; i < n_cand; i += 256)
-      lc[i] = crow[i];
-    src = lc;
+  const bool in_lds = n_cand <= kCandLds;
+  if (in_lds) {
+    for (int i = t; i < n_cand; i += 256) lc[i] = ld_agent(&crow[i]);
   }
   __syncthreads();
-  resolve_candidates(src, n_cand, need, trow + n_above, dh, wtot, bc);
+  if (in_lds) resolve_candidates<false>(lc, n_cand, need, trow + n_above, dh, wtot, bc);
+  else resolve_candidates<true>(crow, n_cand, need, trow + n_above, dh, wtot, bc);
+
+  // leave the row's histogram and counters zeroed for the next call
+  {
+    uint4* hp = reinterpret_cast<uint4*>(gh + t * 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) hp[j] = make_uint4(0, 0, 0, 0);
+    if (t == 0) { ctl[row].n_sel = 0; ctl[row].n_cand = 0; ctl[row].done_sel = 0; }
+  }
 }
 
 // budget >= N: every token is selected
@@ -190,6 +203,12 @@ __global__ __launch_bounds__(256) void select_all_kernel(int32_t* __restrict__ T
   if (n < N) T[(size_t)row * N + n] = n;
 }
 
+// zeroes the histogram and the row counters: 1-D grid, one uint4 per thread
+__global__ __launch_bounds__(256) void ws_clear_kernel(uint4* __restrict__ p, size_t n16) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) p[i] = make_uint4(0, 0, 0, 0);
+}
+
 hipError_t launch_select(const fasa_shape& s, const float* S, const uint32_t* hist, RowCtl* ctl,
                          uint2* cand, int32_t* T, hipStream_t st) {
   const int rows = s.batch * s.n_kv_heads;
@@ -197,9 +216,17 @@ hipError_t launch_select(const fasa_shape& s, const float* S, const uint32_t* hi
     dim3 grid((s.n_ctx + 255) / 256, rows), block(256);
     return launch("fasa_select_all", select_all_kernel, grid, block, st, T, s.n_ctx);
   }
-  dim3 grid((s.n_ctx + kSelTokPerBlock - 1) / kSelTokPerBlock, rows), block(256);
-  return launch("fasa_select", select_kernel, grid, block, st, S, hist, ctl, cand, T, s.n_ctx,
-                s.n_cap, s.budget);
+  const int nslices = (s.n_ctx + kSelTokPerBlock - 1) / kSelTokPerBlock;
+  return launch("fasa_select", select_kernel, dim3(rows * nslices), dim3(256), st, S,
+                const_cast<uint32_t*>(hist), ctl, cand, T, rows, nslices, s.n_ctx, s.n_cap, s.budget);
+}
+
+hipError_t launch_ws_clear(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, hipStream_t st) {
+  // histogram and counters are adjacent in the workspace: [hist | ctl]
+  const size_t bytes = (size_t)((char*)(ctl + s.batch * s.n_kv_heads) - (char*)hist);
+  const size_t n16 = bytes / 16;
+  return launch("fasa_ws_clear", ws_clear_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), st,
+                (uint4*)hist, n16);
 }
 
 }  // namespace fasa

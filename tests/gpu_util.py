@@ -48,8 +48,9 @@ class Device:
         self.shape = self.make_shape()
         self.ws_bytes = fb.fasa_workspace_bytes(self.shape)
         assert self.ws_bytes > 0
-        # poisoned workspace: the library must not rely on a zeroed one
+        # poisoned, then prepared by the library itself: it may not rely on the allocator's zeros
         self.ws = torch.full((self.ws_bytes,), 0x5A, dtype=torch.uint8, device="cuda")
+        fb.fasa_workspace_init(self.shape, self.ws, self.ws_bytes)
 
     def make_shape(self, n_ctx=None, budget=None):
         w = self.w

@@ -25,7 +25,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = _declared()
-    assert len(names) >= 15 and "fasa_decode_step" in names and "fasa_pack_kcache" in names
+    assert len(names) >= 16 and "fasa_decode_step" in names and "fasa_pack_kcache" in names
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -123,6 +123,8 @@ def test_workspace_too_small():
     need = fb.fasa_workspace_bytes(s)
     L = fb.lib
     assert L.fasa_topk(C.byref(s), A, A, A, need - 1, None) == fb.FASA_EWORKSPACE
+    assert L.fasa_workspace_init(C.byref(s), A, need - 1, None) == fb.FASA_EWORKSPACE
+    assert L.fasa_workspace_init(C.byref(s), None, need, None) == fb.FASA_EINVAL
     assert L.fasa_sparse_attend(C.byref(s), A, A, A, A, A, A, 16, None) == fb.FASA_EWORKSPACE
     assert L.fasa_decode_step(C.byref(s), A, A, A, A, A, None, None, A, A, A, A, 0, None) == fb.FASA_EWORKSPACE
 

@@ -163,6 +163,11 @@ def test_growing_cache_appends(fb):
     K, V = x["K"].copy(), x["V"].copy()
     d = Device(w, x)
     d.T = torch.full((w.batch, w.n_kv_heads, W.budget_fraction(3000 + steps)), -1, dtype=torch.int32, device="cuda")
+    # one workspace for the whole loop: sized for the largest step, prepared once
+    d.ws_bytes = max(fb.fasa_workspace_bytes(d.make_shape(n_ctx=3000 + s, budget=W.budget_fraction(3000 + s)))
+                     for s in range(steps + 1))
+    d.ws = torch.full((d.ws_bytes,), 0x77, dtype=torch.uint8, device="cuda")
+    fb.fasa_workspace_init(d.shape, d.ws, d.ws_bytes)
     d.pack()
     n = w.n_ctx
     run_step(fb, w, x, d=d, n_ctx=n, budget=W.budget_fraction(n))
