@@ -45,9 +45,11 @@ __device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t v) {
   return v;
 }
 
-// Inclusive suffix sum over a 256-thread block (thread t gets the sum over threads >= t).
-// `wtot` is a 4-entry LDS scratch.  Contains two block barriers.
-__device__ __forceinline__ uint32_t block256_suffix_sum(uint32_t v, uint32_t* wtot) {
+// Inclusive suffix sum over a block of NT threads (thread t gets the sum over threads >= t).
+// `wtot` is an LDS scratch of NT / 64 entries.  Contains two block barriers.
+template <int NT>
+__device__ __forceinline__ uint32_t block_suffix_sum(uint32_t v, uint32_t* wtot) {
+  constexpr int NW = NT / kWave;
   const int wave = (int)(threadIdx.x >> 6);
   uint32_t s = wave_suffix_sum(v);
   __syncthreads();  // protects wtot against a previous use
@@ -55,9 +57,32 @@ __device__ __forceinline__ uint32_t block256_suffix_sum(uint32_t v, uint32_t* wt
   __syncthreads();
   uint32_t add = 0;
 #pragma unroll
-  for (int w = 1; w < 4; ++w)
+  for (int w = 1; w < NW; ++w)
     if (w > wave) add += wtot[w];
   return s + add;
+}
+__device__ __forceinline__ uint32_t block256_suffix_sum(uint32_t v, uint32_t* wtot) {
+  return block_suffix_sum<256>(v, wtot);
+}
+
+// Exclusive prefix sum over a block of NT threads; `total` gets the block sum.
+// `wtot` is an LDS scratch of NT / 64 entries.  Contains two block barriers.
+template <int NT>
+__device__ __forceinline__ uint32_t block_prefix_sum(uint32_t v, uint32_t* wtot, uint32_t& total) {
+  constexpr int NW = NT / kWave;
+  const int wave = (int)(threadIdx.x >> 6);
+  const uint32_t incl = wave_prefix_sum(v);
+  __syncthreads();
+  if (lane_id() == kWave - 1) wtot[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0;
+  total = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    if (w < wave) before += wtot[w];
+    total += wtot[w];
+  }
+  return before + incl - v;
 }
 
 // Exclusive prefix over a 256-thread block of two counters at once; also returns the block totals.

@@ -9,7 +9,7 @@
 //            and go straight to T, tokens inside it are appended to a candidate list; positions
 //            come from a block-wide prefix sum plus ONE atomic per workgroup and counter;
 //   final    the last workgroup of the row to finish resolves the candidates exactly: radix
-//            select, 8 bits a pass, over the 56-bit composite (low 20 key bits : ~index), which
+//            select, 8 bits a pass, over the 52-bit composite (low 20 key bits : ~index), which
 //            is unique per token, so exactly B - |winners| candidates come out.  It then zeroes
 //            the row's histogram and counters, which leaves the workspace clean for the next call.
 #include "fasa_device.h"
@@ -27,43 +27,44 @@ __device__ __forceinline__ unsigned long long cand_composite(uint2 c) {
 
 // Exact selection of the `need` largest composites among cand[0..n).  Whole block participates.
 // SHARED_SRC: the list lives in global memory and was written by other workgroups.
-template <bool SHARED_SRC>
+template <bool SHARED_SRC, int NT>
 __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* out,
-                                   uint32_t* dh /*256*/, uint32_t* wtot /*4*/,
+                                   uint32_t* dh /*256*/, uint32_t* wtot /*NT/64*/,
                                    uint32_t* bc /*4: digit, need, count, out counter*/) {
   const int t = threadIdx.x;
   const uint32_t out_cap = (uint32_t)need;  // never write past the row's share of T
   unsigned long long prefix = 0;
-  int shift = 56;
+  int shift = 52;            // the composite has 52 significant bits: digits at 44, 36, ..., 4, 0
   if (need < n) {
     while (shift > 0) {
-      shift -= 8;
-      dh[t] = 0;
+      const int width = shift >= 8 ? 8 : shift;   // the last digit is the 4 bits left over
+      shift -= width;
+      if (t < 256) dh[t] = 0;
       __syncthreads();
-      for (int i = t; i < n; i += 256) {
+      for (int i = t; i < n; i += NT) {
         const unsigned long long c = cand_composite(SHARED_SRC ? ld_agent(&cand[i]) : cand[i]);
-        if ((c >> (shift + 8)) == prefix) atomicAdd(&dh[(uint32_t)(c >> shift) & 0xFFu], 1u);
+        if ((c >> (shift + width)) == prefix) atomicAdd(&dh[(uint32_t)(c >> shift) & ((1u << width) - 1u)], 1u);
       }
       __syncthreads();
-      const uint32_t cnt = dh[t];
-      const uint32_t incl = block256_suffix_sum(cnt, wtot);
+      const uint32_t cnt = t < 256 ? dh[t] : 0u;
+      const uint32_t incl = block_suffix_sum<NT>(cnt, wtot);
       const uint32_t excl = incl - cnt;
-      if (excl < (uint32_t)need && (uint32_t)need <= incl) {
+      if (t < 256 && excl < (uint32_t)need && (uint32_t)need <= incl) {
         bc[0] = (uint32_t)t;
         bc[1] = (uint32_t)need - excl;
         bc[2] = cnt;
       }
       __syncthreads();
-      prefix = (prefix << 8) | bc[0];
+      prefix = (prefix << width) | bc[0];
       need = (int)bc[1];
       const uint32_t in_digit = bc[2];
       __syncthreads();
       if ((uint32_t)need == in_digit) break;  // everything under this prefix is a winner
     }
   } else {
-    shift = 56;  // take all: (c >> 56) == 0 >= 0
+    shift = 52;  // take all: (c >> 52) == 0 >= 0
   }
-  for (int i = t; i < n; i += 256) {
+  for (int i = t; i < n; i += NT) {
     const uint2 c = SHARED_SRC ? ld_agent(&cand[i]) : cand[i];
     if ((cand_composite(c) >> shift) >= prefix) {
       const uint32_t pos = atomicAdd(&bc[3], 1u);
@@ -184,8 +185,8 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
     for (int i = t; i < n_cand; i += 256) lc[i] = ld_agent(&crow[i]);
   }
   __syncthreads();
-  if (in_lds) resolve_candidates<false>(lc, n_cand, need, trow + n_above, dh, wtot, bc);
-  else resolve_candidates<true>(crow, n_cand, need, trow + n_above, dh, wtot, bc);
+  if (in_lds) resolve_candidates<false, 256>(lc, n_cand, need, trow + n_above, dh, wtot, bc);
+  else resolve_candidates<true, 256>(crow, n_cand, need, trow + n_above, dh, wtot, bc);
 
   // leave the row's histogram and counters zeroed for the next call
   {

@@ -122,6 +122,7 @@ TOPK_SHAPES = [  # (rows as Bt,Hkv), N, B
     ((1, 1), 4096, 256), ((1, 8), 32768 // 4 + 13, 2048 // 4), ((2, 3), 1000, 1), ((1, 2), 1000, 999),
     ((1, 2), 1000, 1000), ((1, 2), 1000, 5000), ((1, 1), 1, 1), ((1, 1), 63, 7), ((1, 1), 65, 64),
     ((3, 4), 2049, 100), ((1, 1), 20000, 6193 * 20000 // 32768),
+    ((1, 2), 70001, 300), ((1, 8), 40000, 7000),      # several workgroups per row / chunked single workgroup
 ]
 
 
