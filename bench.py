@@ -37,7 +37,13 @@ LLC_BYTES = 256 << 20         # last-level (memory-side) cache the rotation has 
 # HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
 # what the same counters read for a plain copy kernel of known size (see profiles/).  Keyed by
 # (workload config id, kernel name); bytes per launch.  None = not measured yet.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/decode_step_llama3_8b_layer_n32768_b2048_hbm_counters.txt
+    (1, "fasa_score_hist"): 16864778 + 1235328,
+    (1, "fasa_select"): 1354389 + 360859,
+    (1, "fasa_sparse_attend"): 9198340 + 614656,
+    (1, "fasa_dense_attend"): 136543149 + 2408704,
+}
 
 
 def log(*a):
@@ -53,6 +59,8 @@ def main():
     ap.add_argument("--sets", type=int, default=0, help="buffer sets to rotate over (0 = derive)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only plain device copies of known size (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the hot path shards by batch / KV head with no "
@@ -66,6 +74,18 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        # 8 rotating 256 MiB copies: under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` the copy kernel's
+        # counter value per dispatch, divided by 256 MiB, is the scale of the counter on this machine
+        nbytes = 256 << 20
+        src = [torch.full((nbytes,), i, dtype=torch.uint8, device="cuda") for i in range(4)]
+        dst = [torch.empty((nbytes,), dtype=torch.uint8, device="cuda") for _ in range(4)]
+        torch.cuda.synchronize()
+        for i in range(8):
+            dst[i % 4].copy_(src[i % 4])
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": nbytes, "copies": 8}), flush=True)
+        return
     w = W.WORKLOADS[args.config]
     rows = w.batch * w.n_kv_heads
     model = W.algorithmic_bytes(w)
@@ -188,6 +208,7 @@ def main():
         if name in alg_bytes:
             ent["alg_bytes"] = alg_bytes[name]
             ent["gbps"] = round(alg_bytes[name] / us / 1e3, 1)
+            ent["traffic"] = MEASURED_TRAFFIC.get((w.config_id, name))
         kernels[name] = ent
     path_kernels = [k for k in prof if k in alg_bytes]
     dom = max(path_kernels, key=lambda k: alg_bytes[k])      # the kernel that moves the most bytes
