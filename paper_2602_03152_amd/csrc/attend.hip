@@ -51,6 +51,22 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
   constexpr int D = kHeadDim;
   const int t = threadIdx.x;
   const size_t rbase = (size_t)row * n_splits * G;
+  const int dim = t & (D - 1), half = t >> 7;
+  const float* pa = part_acc + rbase * D + dim;
+  // the weighted-V partials of the first 16 splits are requested before anything else: they do
+  // not depend on the weights, so one memory round trip covers both passes
+  float x[8][G];
+  auto load_round = [&](int s0) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = s0 + 2 * u;
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+        x[u][g] = (s < n_splits) ? ld_agent(&pa[((size_t)s * G + g) * D]) : 0.f;
+    }
+  };
+  load_round(half);
+
   // one wave per query head (round-robin): max, then weights, then their sum
   const int wave = t >> 6, lane = t & 63;
   for (int g = wave; g < G; g += 4) {
@@ -83,20 +99,11 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
     if (lane == 0) red[g] = 1.0f / sum;
   }
   __syncthreads();
-  const int dim = t & (D - 1), half = t >> 7;
   float a[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) a[g] = 0.f;
-  const float* pa = part_acc + rbase * D + dim;
   for (int s0 = half; s0 < n_splits; s0 += 16) {
-    float x[8][G];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int s = s0 + 2 * u;
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-        x[u][g] = (s < n_splits) ? ld_agent(&pa[((size_t)s * G + g) * D]) : 0.f;
-    }
+    if (s0 != half) load_round(s0);
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int s = s0 + 2 * u;
@@ -296,6 +303,222 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
   combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, wsm, red, &sm_acc[0][0][0]);
 }
 
+// ---------------------------------------------------------------------------------------------
+// bf16 variant with the logits on the matrix cores.  For a GQA group the logits of 16 gathered
+// rows are the 16x16 product K_tile (16 rows x 128 dims) . Q^T (128 dims x G, padded to 16): four
+// v_mfma_f32_16x16x32_bf16, whose A operand wants exactly one 16-byte chunk of a K row per lane.
+// That removes the per-row cross-lane reductions and the G-fold multiply-adds of the vector
+// version; the weighted sum of V stays on the vector ALUs (a row-major V row cannot be fed to an
+// MFMA operand without a transpose), with the weights handed over through LDS.
+//   K tile, lane (tok = lane & 15, j = lane >> 4): chunks j, j+4, j+8, j+12 of row tok
+//   logits C, lane (g = lane & 15, j): rows 4j..4j+3 of the tile for query head g
+//   V tile, lane (r = lane >> 4, c = lane & 15): head dims 8c..8c+7 of rows r, r+4, r+8, r+12
+// ---------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <int G, bool DENSE>
+__global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __restrict__ q,
+                                                          const uint16_t* __restrict__ K,
+                                                          const uint16_t* __restrict__ V,
+                                                          const int32_t* __restrict__ T,
+                                                          float* __restrict__ O,
+                                                          RowCtl* __restrict__ ctl,
+                                                          float* __restrict__ part_acc,
+                                                          float* __restrict__ part_ml, int rows,
+                                                          int n_splits, int Hq, int Hkv, int count,
+                                                          int n_ctx, int tok_per_split, long long sb,
+                                                          long long sh, long long sn,
+                                                          float scale_log2e) {
+  constexpr int D = kHeadDim;
+  __shared__ float sm_m[4][G], sm_l[4][G];
+  __shared__ float sm_acc[4][G][D];
+  __shared__ float wsm[G * kMaxSplitsLds];
+  __shared__ float red[G];
+  __shared__ uint32_t ticket;
+  __shared__ __align__(16) float pt[4][16][8];   // per wave: weights of the tile, [row][query head]
+  __shared__ __align__(16) float scs[4][8];      // per wave: rescale factor of the running sums
+
+  int row, split;
+  row_slice_of_block(rows, n_splits, row, split);
+  const int b = row / Hkv, h = row % Hkv;
+  const int t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
+  const int lo = lane & 15, hi = lane >> 4;
+
+  const int s0 = split * tok_per_split;
+  const int s1 = min(count, s0 + tok_per_split);
+
+  // B operands: Q^T, column g = lo (zero beyond G), k-slots (hi, 0..7) of MFMA i = dims 8(hi+4i)..+7
+  bf16x8_t qb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (lo < G) v = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + (size_t)h * G + lo) * D + 8 * (hi + 4 * i));
+    qb[i] = __builtin_bit_cast(bf16x8_t, v);
+  }
+  float acc[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[g][k] = 0.f;
+  float m_run = kNegBig, l_run = 0.f;   // of query head lo, over this lane's rows of every tile
+
+  const uint16_t* Kb = K + b * sb + h * sh;
+  const uint16_t* Vb = V + b * sb + h * sh + 8 * lo;
+  const int32_t* Trow = DENSE ? nullptr : T + (size_t)row * count;
+
+  for (int j0 = s0 + wave * 16; j0 < s1; j0 += 64) {
+    // The scaled logit is rounded once and that rounded value is what the running maximum and the
+    // exponent see: the scaling is never fused into the subtraction of the maximum (the weight of
+    // the maximal row must be exactly 1).  Explicit fmaf calls below are not affected.
+#pragma clang fp contract(off)
+    // ---- gather: one K row per lane column, four V rows per lane group ----
+    long long koff;
+    {
+      const int j = j0 + lo;
+      const int jj = j < s1 ? j : s0;
+      const int tok = DENSE ? jj : min(max(Trow[jj], 0), n_ctx - 1);
+      koff = (long long)tok * sn;
+    }
+    long long voff[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + 4 * u + hi;
+      const int jj = j < s1 ? j : s0;
+      const int tok = DENSE ? jj : min(max(Trow[jj], 0), n_ctx - 1);
+      voff[u] = (long long)tok * sn;
+    }
+    uint4 kc[4], vc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) kc[i] = *reinterpret_cast<const uint4*>(Kb + koff + 8 * (hi + 4 * i));
+#pragma unroll
+    for (int u = 0; u < 4; ++u) vc[u] = *reinterpret_cast<const uint4*>(Vb + voff[u]);
+
+    // ---- logits of the tile: rows 4hi..4hi+3, query head lo ----
+    f32x4_t c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kc[i]), qb[i], c, 0, 0, 0);
+
+    float sv[4];
+    bool valid[4];
+    float mx = kNegBig;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      valid[e] = j0 + 4 * hi + e < s1;
+      sv[e] = c[e] * scale_log2e;
+      mx = valid[e] ? fmaxf(mx, sv[e]) : mx;
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    const float m_new = fmaxf(m_run, mx);
+    const float sc = exp2f(m_run - m_new);
+    m_run = m_new;
+    float psum = 0.f;
+    float pv[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      pv[e] = valid[e] ? exp2f(sv[e] - m_new) : 0.f;
+      psum += pv[e];
+    }
+    l_run = fmaf(l_run, sc, psum);
+    if (lo < 8) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pt[wave][4 * hi + e][lo] = pv[e];
+      if (hi == 0) scs[wave][lo] = sc;
+    }
+    // same wave writes and reads: LDS operations of a wave complete in order; the fence only keeps
+    // the compiler from moving the reads above the writes
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // ---- weighted sum of V on the vector ALUs ----
+    float scg[8];
+    {
+      const float4 a0 = *reinterpret_cast<const float4*>(&scs[wave][0]);
+      const float4 a1 = *reinterpret_cast<const float4*>(&scs[wave][4]);
+      scg[0] = a0.x; scg[1] = a0.y; scg[2] = a0.z; scg[3] = a0.w;
+      scg[4] = a1.x; scg[5] = a1.y; scg[6] = a1.z; scg[7] = a1.w;
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc[g][k] *= scg[g];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float pg[8];
+      const float4 p0 = *reinterpret_cast<const float4*>(&pt[wave][4 * u + hi][0]);
+      pg[0] = p0.x; pg[1] = p0.y; pg[2] = p0.z; pg[3] = p0.w;
+      if (G > 4) {
+        const float4 p1 = *reinterpret_cast<const float4*>(&pt[wave][4 * u + hi][4]);
+        pg[4] = p1.x; pg[5] = p1.y; pg[6] = p1.z; pg[7] = p1.w;
+      }
+      float vf[8];
+      vf[0] = bf16_lo(vc[u].x); vf[1] = bf16_hi(vc[u].x); vf[2] = bf16_lo(vc[u].y); vf[3] = bf16_hi(vc[u].y);
+      vf[4] = bf16_lo(vc[u].z); vf[5] = bf16_hi(vc[u].z); vf[6] = bf16_lo(vc[u].w); vf[7] = bf16_hi(vc[u].w);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[g][k] = fmaf(pg[g], vf[k], acc[g][k]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();   // the tile's weights are consumed before the next tile overwrites them
+  }
+
+  // ---- wave totals: sum of weights over the 4 lane groups, weighted V over the 4 row groups ----
+  l_run += __shfl_xor(l_run, 16, kWave);
+  l_run += __shfl_xor(l_run, 32, kWave);
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      acc[g][k] += __shfl_xor(acc[g][k], 16, kWave);
+      acc[g][k] += __shfl_xor(acc[g][k], 32, kWave);
+    }
+  if (hi == 0) {
+    if (lo < G) { sm_m[wave][lo] = m_run; sm_l[wave][lo] = l_run; }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) sm_acc[wave][g][8 * lo + k] = acc[g][k];
+  }
+  __syncthreads();
+
+  // merge the 4 waves; one (query head, head dim) per thread and pass
+  const size_t pbase = ((size_t)row * n_splits + split) * G;
+  for (int i = t; i < G * D; i += 256) {
+    const int g = i / D, dim = i % D;
+    float mn = sm_m[0][g];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) mn = fmaxf(mn, sm_m[w][g]);
+    float ls = 0.f, a = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float sc = exp2f(sm_m[w][g] - mn);
+      ls = fmaf(sm_l[w][g], sc, ls);
+      a = fmaf(sm_acc[w][g][dim], sc, a);
+    }
+    if (n_splits == 1) {
+      O[((size_t)b * Hq + (size_t)h * G + g) * D + dim] = a / ls;
+    } else {
+      st_agent(&part_acc[(pbase + g) * D + dim], a);
+      if (dim == 0) {
+        st_agent(&part_ml[(pbase + g) * 2], mn);
+        st_agent(&part_ml[(pbase + g) * 2 + 1], ls);
+      }
+    }
+  }
+  if (n_splits == 1) return;
+  publish_barrier();
+  if (t == 0) ticket = atomicAdd(&ctl[row].done_att, 1u);
+  __syncthreads();
+  if (ticket != (uint32_t)n_splits - 1u) return;
+  if (t == 0) ctl[row].done_att = 0;
+  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, wsm, red, &sm_acc[0][0][0]);
+}
+
 template <typename ET, int G>
 static hipError_t launch_attend_g(const fasa_shape& s, bool dense, const AttendPlan& p,
                                   const void* q, const void* K, const void* V, const int32_t* T,
@@ -304,6 +527,19 @@ static hipError_t launch_attend_g(const fasa_shape& s, bool dense, const AttendP
   const int rows = s.batch * s.n_kv_heads;
   dim3 grid(rows * p.n_splits), block(256);
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)s.head_dim);
+  if constexpr (sizeof(ET) == 2) {
+    if (dense)
+      return launch("fasa_dense_attend", attend_mfma_kernel<G, true>, grid, block, st,
+                    (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, T, O, ctl, part_acc,
+                    part_ml, rows, p.n_splits, s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx,
+                    p.tok_per_split, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
+                    (long long)s.kv_stride_n, scale_log2e);
+    return launch("fasa_sparse_attend", attend_mfma_kernel<G, false>, grid, block, st,
+                  (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, T, O, ctl, part_acc,
+                  part_ml, rows, p.n_splits, s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx,
+                  p.tok_per_split, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
+                  (long long)s.kv_stride_n, scale_log2e);
+  }
   if (dense)
     return launch("fasa_dense_attend", attend_kernel<ET, G, true>, grid, block, st, (const ET*)q,
                   (const ET*)K, (const ET*)V, T, O, ctl, part_acc, part_ml, rows, p.n_splits,

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
                                                      int N, int n_cap, int bsel) {
   __shared__ uint32_t wtot[8];
   __shared__ uint32_t bc[4];
-  __shared__ uint32_t thr[2];  // threshold bin, tokens above it
+  __shared__ uint32_t thr[3];  // threshold bin, tokens above it, tokens inside it
   __shared__ uint32_t dh[256];
   __shared__ uint2 lc[kCandLds];
 
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
 
   // ---- threshold bin from the coarse histogram (every workgroup of the row redoes this) ----
   uint32_t* gh = hist + (size_t)row * kHistBins;
-  if (t == 0) { thr[0] = 0; thr[1] = 0; }
+  if (t == 0) { thr[0] = 0; thr[1] = 0; thr[2] = 0; }
   {
     uint32_t hb[16];
     const uint4* hp = reinterpret_cast<const uint4*>(gh + t * 16);
@@ -128,6 +128,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
         if (cum < (uint32_t)bsel && cum + hb[j] >= (uint32_t)bsel) {
           thr[0] = (uint32_t)(t * 16 + j);
           thr[1] = cum;
+          thr[2] = hb[j];
         }
         cum += hb[j];
       }
@@ -176,8 +177,8 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   const bool last = bc[2] == (uint32_t)nslices - 1u;
   __syncthreads();
   if (!last) return;
-  int n_cand = (int)ld_agent(&ctl[row].n_cand);
-  n_cand = min(n_cand, n_cap);
+  // the candidates are exactly the tokens of the threshold bin: their number is in the histogram
+  const int n_cand = (int)min(thr[2], (uint32_t)n_cap);
   const int need = max(0, min(bsel - (int)n_above, n_cand));
   if (t == 0) bc[3] = 0;
   const bool in_lds = n_cand <= kCandLds;
