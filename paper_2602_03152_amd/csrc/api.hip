@@ -58,15 +58,28 @@ static int profile_fold() {
 // ---------------------------------------------------------------------------------------------
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-AttendPlan plan_attend(int rows, int count) {
-  // aim at ~1024 workgroups over the chip, at least one 64-token batch round per workgroup
+AttendPlan plan_attend(int rows, int count, int group) {
+  // The attention kernels are gather-bound and all their workgroups should be resident at once:
+  // a second, partly filled round of workgroups costs as much as a full one.  MI355X has 256 CUs;
+  // the kernels' register use (112 VGPRs at a GQA group of 4, 136 at 7) allows 4 workgroups per CU
+  // up to a group of 5 and 3 above.
+  const long long slots = 256LL * (group <= 5 ? 4 : 3);
   const long long total = (long long)rows * count;
-  long long tps = (total + 1023) / 1024;
-  tps = ((tps + 63) / 64) * 64;
-  if (tps < 64) tps = 64;
+  const long long by_size = (total + 63) / 64;           // workgroups of at least 64 list entries
+  long long nblocks;
+  if (by_size <= slots) {
+    nblocks = by_size;                                    // small problem: one partial round
+  } else {
+    const long long rounds = (total + slots * 2048 - 1) / (slots * 2048);   // <= ~2048 entries each
+    nblocks = rounds * slots;
+  }
+  long long n_splits = (nblocks + rows / 2) / rows;
+  if (n_splits < 1) n_splits = 1;
+  if (n_splits > 256) n_splits = 256;                     // the merging workgroup weights <= 256 splits
+  if (n_splits > (count + 15) / 16) n_splits = (count + 15) / 16;
+  const long long tps = (count + n_splits - 1) / n_splits;
   AttendPlan p;
   p.count = count;
-  if ((count + tps - 1) / tps > 256) tps = (((count + 255) / 256 + 63) / 64) * 64;  // <= 256 splits a row
   p.tok_per_split = (int)tps;
   p.n_splits = (int)((count + tps - 1) / tps);
   return p;
@@ -77,8 +90,8 @@ WsLayout ws_layout(const fasa_shape& s) {
   w.rows = s.batch * s.n_kv_heads;
   const int G = s.n_q_heads / s.n_kv_heads;
   const int bsel = s.budget < s.n_ctx ? s.budget : s.n_ctx;
-  const int sp_sparse = plan_attend(w.rows, bsel).n_splits;
-  const int sp_dense = plan_attend(w.rows, s.n_ctx).n_splits;
+  const int sp_sparse = plan_attend(w.rows, bsel, G).n_splits;
+  const int sp_dense = plan_attend(w.rows, s.n_ctx, G).n_splits;
   w.max_splits = sp_sparse > sp_dense ? sp_sparse : sp_dense;
   size_t off = 0;
   w.hist_off = off;      off = align256(off + (size_t)w.rows * kHistBins * sizeof(uint32_t));

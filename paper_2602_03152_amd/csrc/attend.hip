@@ -576,7 +576,7 @@ hipError_t launch_attend(const fasa_shape& s, bool dense, const void* q, const v
                          float* part_ml, hipStream_t st) {
   const int rows = s.batch * s.n_kv_heads;
   const int count = dense ? s.n_ctx : (s.budget < s.n_ctx ? s.budget : s.n_ctx);
-  const AttendPlan p = plan_attend(rows, count);
+  const AttendPlan p = plan_attend(rows, count, s.n_q_heads / s.n_kv_heads);
   return s.dtype == FASA_BF16
              ? launch_attend_t<uint16_t>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st)
              : launch_attend_t<float>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);

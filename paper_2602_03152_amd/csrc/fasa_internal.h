@@ -41,11 +41,11 @@ struct WsLayout {
 
 struct AttendPlan {
   int count;          // tokens attended per row
-  int tok_per_split;  // multiple of 64
+  int tok_per_split;  // list entries per workgroup
   int n_splits;
 };
 
-AttendPlan plan_attend(int rows, int count);
+AttendPlan plan_attend(int rows, int count, int group);
 WsLayout ws_layout(const fasa_shape& s);
 
 // ---------------------------------------------------------------------------------------------

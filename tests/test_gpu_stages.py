@@ -235,6 +235,32 @@ def test_attend_invariants_that_expose_dropped_or_doubled_rows(fb):
             np.testing.assert_array_equal(got[b, hq].astype(np.float64), V64[b, hq // G, T1[b, hq // G, 0]])
 
 
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_every_gqa_group_size(fb, G, dtype):
+    """All template instances of the attention kernels (group sizes 1..8, both storage types), with a
+    ragged list length, plus the fused step on the same shape."""
+    from tests.gpu_util import to_host
+    w = W.WORKLOADS[1].scaled(batch=2, n_kv_heads=3, n_q_heads=3 * G, n_ctx=1900 + G, budget=150 + 3 * G,
+                              n_fc=5 + 4 * G, dtype=dtype)
+    x = W.make_inputs(w, n_cap=(w.n_ctx + 63) // 64 * 64)
+    d = _dev(w, x)
+    d.pack()
+    print("gqa", G, dtype, flush=True)
+    fb.fasa_decode_step(d.shape, d.q, d.K, d.V, d.Kp, d.fc_idx, None, None, d.S, d.T, d.O, d.ws, d.ws_bytes)
+    torch.cuda.synchronize()
+    S_ref, D_ref = O.score(x["q"], x["K"], x["fc_idx"], w.n_ctx)
+    S = to_host(d.S)[:, :, :w.n_ctx].astype(np.float64)
+    assert np.all(np.abs(S - S_ref) <= SCORE_RTOL * np.maximum(np.abs(S_ref), D_ref))
+    T = np.sort(to_host(d.T), -1)
+    np.testing.assert_array_equal(T, O.topk(to_host(d.S)[:, :, :w.n_ctx], w.budget, w.n_ctx))   # same float32 scores
+    ref = O.sparse_attend(x["q"], x["K"], x["V"], T)
+    assert np.abs(to_host(d.O) - ref).max() <= OUT_ATOL
+    fb.fasa_dense_attend(d.shape, d.q, d.K, d.V, d.O, d.ws, d.ws_bytes)
+    torch.cuda.synchronize()
+    assert np.abs(to_host(d.O) - O.dense_attend(x["q"], x["K"], x["V"], w.n_ctx)).max() <= OUT_ATOL
+
+
 def test_strided_kv_cache(fb):
     """K and V living in a larger allocation (row pitch 160 elements, head/batch pitches padded)."""
     from tests.gpu_util import to_host, to_dev
