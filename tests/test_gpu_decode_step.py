@@ -120,6 +120,34 @@ def test_all_fcs_full_budget_is_dense_attention(fb):
     assert np.abs(to_host(d.O) - out).max() <= 1e-5
 
 
+def test_full_head_ranking_and_recall(fb):
+    """The paper's "Oracle" baseline ranks by full-head scores (all d/2 FCs).  With the same kernels
+    at F = d/2 the device's top-B set and the recall of the dominant-FC selection against it must
+    equal what the CPU oracle gets."""
+    from tests.gpu_util import Device, to_host, to_dev
+    w = W.WORKLOADS[1].scaled(n_ctx=4000 + 3, budget=250, n_kv_heads=4, n_q_heads=16)
+    x = W.make_inputs(w, n_cap=4032)
+    d = run_step(fb, w, x)
+    T_dom = np.sort(to_host(d.T), -1)
+    half = w.head_dim // 2
+    w_all = w.scaled(n_fc=half)
+    x_all = dict(x); x_all["fc_idx"] = np.tile(np.arange(half, dtype=np.int32), (w.n_kv_heads, 1))
+    e = run_step(fb, w_all, x_all)
+    T_all = np.sort(to_host(e.T), -1)
+    S_all_ref, D_all = O.score(x["q"], x["K"], x_all["fc_idx"], w.n_ctx)
+    full = np.einsum("bhgd,bhnd->bhn", W.storage_to_f64(x["q"]).reshape(1, 4, 4, 128), W.storage_to_f64(x["K"])[:, :, :w.n_ctx])
+    np.testing.assert_allclose(S_all_ref, full, rtol=0, atol=1e-9)
+    n_diff = check_selection(S_all_ref, D_all, T_all, w.budget, w.n_ctx)
+    S_dom_ref, _ = O.score(x["q"], x["K"], x["fc_idx"], w.n_ctx)
+    T_dom_ref = O.topk(S_dom_ref.astype(np.float32), w.budget, w.n_ctx)
+    T_all_ref = O.topk(S_all_ref.astype(np.float32), w.budget, w.n_ctx)
+    rec_ref = np.mean([len(np.intersect1d(T_dom_ref[0, h], T_all_ref[0, h])) / w.budget for h in range(4)])
+    rec_gpu = np.mean([len(np.intersect1d(T_dom[0, h], T_all[0, h])) / w.budget for h in range(4)])
+    print("  recall oracle %.4f device %.4f (sets differ on %d tokens)" % (rec_ref, rec_gpu, n_diff), flush=True)
+    assert abs(rec_ref - rec_gpu) <= (n_diff + 1) / w.budget
+    assert 0.3 < rec_gpu <= 1.0      # 16 of 64 FCs carrying 16x the energy recover most of the full-head top-B
+
+
 def test_fused_equals_staged_calls(fb):
     from tests.gpu_util import Device, to_host
     w = W.WORKLOADS[1].scaled(n_ctx=6000 + 5, budget=500)
