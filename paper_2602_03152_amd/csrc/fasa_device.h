@@ -23,26 +23,30 @@ __device__ __forceinline__ uint32_t score_key(float s) {
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 
-// Inclusive suffix sum over the 64 lanes of a wave: result(lane) = sum of v over lanes >= lane.
-__device__ __forceinline__ uint32_t wave_suffix_sum(uint32_t v) {
-  const int lane = lane_id();
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const uint32_t x = __shfl_down(v, o, kWave);
-    if (lane + o < kWave) v += x;
-  }
+// DPP move of a 32-bit value; lanes without a source keep 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xF, false);
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave, entirely on the vector ALU: Hillis-Steele
+// inside each row of 16 lanes (row_shr 1, 2, 4, 8), then the last lane of row 0/2 is added to row
+// 1/3 (row_bcast15) and the last lane of the lower half to the upper half (row_bcast31).
+__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t v) {
+  v += dpp_u32<0x111, 0xF>(v);
+  v += dpp_u32<0x112, 0xF>(v);
+  v += dpp_u32<0x114, 0xF>(v);
+  v += dpp_u32<0x118, 0xF>(v);
+  v += dpp_u32<0x142, 0xA>(v);
+  v += dpp_u32<0x143, 0xC>(v);
   return v;
 }
 
-// Inclusive prefix sum over the 64 lanes of a wave.
-__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t v) {
-  const int lane = lane_id();
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const uint32_t x = __shfl_up(v, o, kWave);
-    if (lane >= o) v += x;
-  }
-  return v;
+// Inclusive suffix sum over the 64 lanes of a wave: result(lane) = sum of v over lanes >= lane.
+__device__ __forceinline__ uint32_t wave_suffix_sum(uint32_t v) {
+  const uint32_t incl = wave_prefix_sum(v);
+  const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
+  return total - incl + v;
 }
 
 // Inclusive suffix sum over a block of NT threads (thread t gets the sum over threads >= t).

@@ -58,7 +58,7 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
       prefix = (prefix << width) | bc[0];
       need = (int)bc[1];
       const uint32_t in_digit = bc[2];
-      __syncthreads();
+      // no barrier needed here: bc is next written three barriers into the following pass
       if ((uint32_t)need == in_digit) break;  // everything under this prefix is a winner
     }
   } else {
@@ -91,6 +91,9 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   const int t = threadIdx.x;
   const float* s = S + (size_t)row * n_cap;
   const int base = slice * kSelTokPerBlock;
+#ifdef FASA_TRACE
+  unsigned long long tt[8]; for (int i = 0; i < 8; ++i) tt[i] = 0; tt[0] = wall_clock64();
+#endif
 
   // ---- this workgroup's scores: loads go out first, the histogram work hides their latency ----
   float v[kSelPerThread];
@@ -137,6 +140,9 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   }
   const uint32_t tbin = thr[0];
   const uint32_t n_above = thr[1];
+#ifdef FASA_TRACE
+  tt[1] = wall_clock64();
+#endif
 
   // ---- classify, then one position range per workgroup and counter ----
   uint32_t key[kSelPerThread];
@@ -157,6 +163,9 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
     bc[1] = tc ? atomicAdd(&ctl[row].n_cand, tc) : 0u;
   }
   __syncthreads();
+#ifdef FASA_TRACE
+  tt[2] = wall_clock64();
+#endif
   uint32_t bw = bc[0] + pw, bcand = bc[1] + pc;
   int32_t* trow = T + (size_t)row * bsel;
   uint2* crow = cand + (size_t)row * n_cap;
@@ -176,6 +185,10 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   __syncthreads();
   const bool last = bc[2] == (uint32_t)nslices - 1u;
   __syncthreads();
+#ifdef FASA_TRACE
+  tt[3] = wall_clock64();
+  if (!last && t == 0 && row == 0 && slice == 0) printf("select blk0: thr %llu pos %llu ticket %llu (x10ns)\n", tt[1]-tt[0], tt[2]-tt[1], tt[3]-tt[2]);
+#endif
   if (!last) return;
   // the candidates are exactly the tokens of the threshold bin: their number is in the histogram
   const int n_cand = (int)min(thr[2], (uint32_t)n_cap);
@@ -186,8 +199,15 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
     for (int i = t; i < n_cand; i += 256) lc[i] = ld_agent(&crow[i]);
   }
   __syncthreads();
+#ifdef FASA_TRACE
+  tt[4] = wall_clock64();
+#endif
   if (in_lds) resolve_candidates<false, 256>(lc, n_cand, need, trow + n_above, dh, wtot, bc);
   else resolve_candidates<true, 256>(crow, n_cand, need, trow + n_above, dh, wtot, bc);
+#ifdef FASA_TRACE
+  tt[5] = wall_clock64();
+  if (t == 0 && row == 0) printf("select last(row0,slice %d): thr %llu pos %llu ticket %llu candload %llu resolve %llu ncand %d need %d (x10ns)\n", slice, tt[1]-tt[0], tt[2]-tt[1], tt[3]-tt[2], tt[4]-tt[3], tt[5]-tt[4], n_cand, need);
+#endif
 
   // leave the row's histogram and counters zeroed for the next call
   {
