@@ -84,8 +84,7 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
     }
 #pragma unroll
     for (int i = 0; i < kMaxSplitsLds / 64; ++i) mx = fmaxf(mx, mv[i]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));
+    mx = wave_max(mx);
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < kMaxSplitsLds / 64; ++i) {
@@ -94,8 +93,7 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
       if (s < n_splits) wsm[g * kMaxSplitsLds + s] = wgt;
       sum = fmaf(lv[i], wgt, sum);
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, kWave);
+    sum = wave_sum(sum);
     if (lane == 0) red[g] = 1.0f / sum;
   }
   __syncthreads();
@@ -241,21 +239,13 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
 
   // merge the 4 groups of the wave (lanes c, c+16, c+32, c+48 hold the same head dims)
 #pragma unroll
-  for (int o = 16; o < 64; o <<= 1) {
+  for (int g = 0; g < G; ++g) {
+    const float mn = xor32_max(xor16_max(m[g]));
+    const float sc = exp2f(m[g] - mn);
+    m[g] = mn;
+    l[g] = xor32_sum(xor16_sum(l[g] * sc));
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const float mo = __shfl_xor(m[g], o, kWave);
-      const float mn = fmaxf(m[g], mo);
-      const float sc = exp2f(m[g] - mn);
-      m[g] = mn;
-      l[g] *= sc;
-      l[g] += __shfl_xor(l[g], o, kWave);
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        acc[g][k] *= sc;
-        acc[g][k] += __shfl_xor(acc[g][k], o, kWave);
-      }
-    }
+    for (int k = 0; k < 8; ++k) acc[g][k] = xor32_sum(xor16_sum(acc[g][k] * sc));
   }
   if (r == 0) {
 #pragma unroll
@@ -348,6 +338,9 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
 
   const int s0 = split * tok_per_split;
   const int s1 = min(count, s0 + tok_per_split);
+#ifdef FASA_TRACE
+  unsigned long long tt[8]; for (int i = 0; i < 8; ++i) tt[i] = 0; tt[0] = wall_clock64();
+#endif
 
   // B operands: Q^T, column g = lo (zero beyond G), k-slots (hi, 0..7) of MFMA i = dims 8(hi+4i)..+7
   bf16x8_t qb[4];
@@ -410,8 +403,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
       sv[e] = c[e] * scale_log2e;
       mx = valid[e] ? fmaxf(mx, sv[e]) : mx;
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    mx = xor32_max(xor16_max(mx));
     const float m_new = fmaxf(m_run, mx);
     const float sc = exp2f(m_run - m_new);
     m_run = m_new;
@@ -467,16 +459,15 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
     __builtin_amdgcn_wave_barrier();   // the tile's weights are consumed before the next tile overwrites them
   }
 
+#ifdef FASA_TRACE
+  tt[1] = wall_clock64();
+#endif
   // ---- wave totals: sum of weights over the 4 lane groups, weighted V over the 4 row groups ----
-  l_run += __shfl_xor(l_run, 16, kWave);
-  l_run += __shfl_xor(l_run, 32, kWave);
+  l_run = xor32_sum(xor16_sum(l_run));
 #pragma unroll
   for (int g = 0; g < G; ++g)
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      acc[g][k] += __shfl_xor(acc[g][k], 16, kWave);
-      acc[g][k] += __shfl_xor(acc[g][k], 32, kWave);
-    }
+    for (int k = 0; k < 8; ++k) acc[g][k] = xor32_sum(xor16_sum(acc[g][k]));
   if (hi == 0) {
     if (lo < G) { sm_m[wave][lo] = m_run; sm_l[wave][lo] = l_run; }
 #pragma unroll
@@ -511,12 +502,23 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
     }
   }
   if (n_splits == 1) return;
+#ifdef FASA_TRACE
+  tt[2] = wall_clock64();
+#endif
   publish_barrier();
   if (t == 0) ticket = atomicAdd(&ctl[row].done_att, 1u);
   __syncthreads();
+#ifdef FASA_TRACE
+  tt[3] = wall_clock64();
+  if (t == 0 && row == 0 && split == 0) printf("attend blk0: tiles %llu merge %llu publish+ticket %llu (x10ns)\n", tt[1]-tt[0], tt[2]-tt[1], tt[3]-tt[2]);
+#endif
   if (ticket != (uint32_t)n_splits - 1u) return;
   if (t == 0) ctl[row].done_att = 0;
   combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, wsm, red, &sm_acc[0][0][0]);
+#ifdef FASA_TRACE
+  tt[4] = wall_clock64();
+  if (t == 0 && row == 0) printf("attend last(row0, split %d): tiles %llu merge %llu publish+ticket %llu combine %llu (x10ns)\n", split, tt[1]-tt[0], tt[2]-tt[1], tt[3]-tt[2], tt[4]-tt[3]);
+#endif
 }
 
 template <typename ET, int G>

@@ -179,4 +179,37 @@ __device__ __forceinline__ float row16_sum(float x) {
   return x;
 }
 
+// max over the 16 lanes of a DPP row
+__device__ __forceinline__ float row16_max(float x) {
+  x = fmaxf(x, dpp_mov<0xB1>(x));
+  x = fmaxf(x, dpp_mov<0x4E>(x));
+  x = fmaxf(x, dpp_mov<0x141>(x));
+  x = fmaxf(x, dpp_mov<0x140>(x));
+  return x;
+}
+
+// Lane exchanges between the four rows of a wave with the gfx950 permlane swaps (vector ALU, no
+// LDS): both results of a swap of x with itself are the two partners of a butterfly step.
+//   v_permlane16_swap: odd rows of the first operand <-> even rows of the second
+//   v_permlane32_swap: upper half of the first operand <-> lower half of the second
+__device__ __forceinline__ float xor16_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float xor32_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float xor16_max(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xor32_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+// reductions over all 64 lanes; every lane gets the result
+__device__ __forceinline__ float wave_sum(float x) { return xor32_sum(xor16_sum(row16_sum(x))); }
+__device__ __forceinline__ float wave_max(float x) { return xor32_max(xor16_max(row16_max(x))); }
+
 }  // namespace fasa
