@@ -131,6 +131,33 @@ int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, v
                      const int32_t* fc_idx, const void* k_new, const void* v_new, float* S,
                      int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- memory-optimised variant (paper Sec. 4.3 and Alg. 2: "FASA-M") -----------------------------
+ * Only the dominant key dims (Kp) stay on the device.  The non-dominant key dims and all values
+ * live in PINNED HOST memory that the device can address (hipHostMalloc / a pinned torch tensor):
+ *     Knd_host [batch][n_kv_heads][n_cap][head_dim - 2*n_fc]   dtype, non-dominant dims of each key,
+ *                                                               ascending dim order
+ *     V_host   [batch][n_kv_heads][tokens][head_dim]           dtype, strides kv_stride_{b,h,n}
+ * Per step the device itself fetches the selected rows over PCIe (Alg. 2: SelectTokens,
+ * TransferToGPU), rebuilds the full key rows from both parts (Combine) into `stage`, a DEVICE
+ * buffer of fasa_offload_stage_bytes(), and runs the same attention over it.  Results equal those
+ * of fasa_decode_step on the same cache (same T; O up to float32 summation order). */
+
+/* Bytes of the device staging buffer for the gathered rows (host-only, pure; 0 on a bad shape). */
+size_t fasa_offload_stage_bytes(const fasa_shape* shape);
+
+/* Alg. 2 Split + UpdateCache for tokens [n_begin, n_end): reads K (DEVICE, strides kv_stride_*),
+ * writes the dominant pairs to Kp (DEVICE) and the remaining dims to Knd_host (HOST, pinned). */
+int fasa_offload_split_kcache(const fasa_shape* shape, const void* K, const int32_t* fc_idx, void* Kp,
+                              void* Knd_host, int32_t n_begin, int32_t n_end, void* stream);
+
+/* One decode step of the memory-optimised variant.  k_new / v_new ([batch][n_kv_heads][head_dim],
+ * DEVICE, both NULL or both set) are split and appended at position n_ctx - 1 first (Alg. 2 order).
+ * Needs a prepared workspace like fasa_decode_step. */
+int fasa_offload_decode_step(const fasa_shape* shape, const void* q, void* Kp, const int32_t* fc_idx,
+                             void* Knd_host, void* V_host, const void* k_new, const void* v_new,
+                             float* S, int32_t* T, float* O, void* ws, size_t ws_bytes, void* stage,
+                             size_t stage_bytes, void* stream);
+
 /* Static description of a status code. */
 const char* fasa_strerror(int status);
 /* hipError_t value of the last failed HIP call on this thread (0 if none). */

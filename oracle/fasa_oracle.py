@@ -148,6 +148,75 @@ def dense_attend(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_ctx: int) -> np.
 
 
 # ------------------------------------------------------------------------------------
+# Alg. 2 (memory-optimised variant): Split / SelectTokens / Combine of the key cache
+# ------------------------------------------------------------------------------------
+def nondominant_dims(fc_idx_h: np.ndarray, d: int) -> np.ndarray:
+    """Head dims of one KV head that belong to no dominant FC, ascending."""
+    dom = set()
+    for i in fc_idx_h:
+        dom.add(int(i)); dom.add(int(i) + d // 2)
+    return np.array([j for j in range(d) if j not in dom], dtype=np.int64)
+
+
+def split_kcache(K: np.ndarray, fc_idx: np.ndarray, n_ctx: int):
+    """Split(k, I_dom) for every cached key: (Kp, Knd).  Kp is the FC-major dominant copy kept on
+    the device; Knd[b,h,n,:] holds the non-dominant dims of key n in ascending dim order (the part
+    the memory-optimised variant keeps in host memory)."""
+    Bt, Hkv, _, d = K.shape
+    F = fc_idx.shape[1]
+    Kp = pack_kcache(K, fc_idx, n_ctx)
+    Knd = np.zeros((Bt, Hkv, n_ctx, d - 2 * F), dtype=K.dtype)
+    for h in range(Hkv):
+        Knd[:, h] = K[:, h, :n_ctx][:, :, nondominant_dims(fc_idx[h], d)]
+    return Kp, Knd
+
+
+def combine_selected(Kp: np.ndarray, Knd: np.ndarray, fc_idx: np.ndarray, T) -> list:
+    """SelectTokens + Combine: the full key rows of the selected tokens rebuilt from the two parts.
+    Returns K_T[b][h] as arrays [len(T[b][h])][d], storage dtype (bit-exact copies)."""
+    Bt, Hkv, F = Kp.shape[0], Kp.shape[1], Kp.shape[2]
+    d = Knd.shape[-1] + 2 * F
+    out = []
+    for b in range(Bt):
+        row = []
+        for h in range(Hkv):
+            idx = np.asarray(T[b][h], dtype=np.int64)
+            k_t = np.zeros((len(idx), d), dtype=Kp.dtype)
+            k_t[:, nondominant_dims(fc_idx[h], d)] = Knd[b, h][idx]
+            for f in range(F):
+                i = int(fc_idx[h, f])
+                k_t[:, i] = Kp[b, h, f, idx, 0]
+                k_t[:, i + d // 2] = Kp[b, h, f, idx, 1]
+            row.append(k_t)
+        out.append(row)
+    return out
+
+
+def attend_on_rows(q: np.ndarray, K_T: list, V_T: list) -> np.ndarray:
+    """FAC on already gathered rows (the last two lines of Alg. 2 before W_O)."""
+    q64 = widen(q)
+    Bt, Hq, d = q64.shape
+    Hkv = len(K_T[0])
+    G = Hq // Hkv
+    O = np.zeros((Bt, Hq, d))
+    for b in range(Bt):
+        for h in range(Hkv):
+            k64, v64 = widen(K_T[b][h]), widen(V_T[b][h])
+            for g in range(G):
+                logits = (k64 @ q64[b, h * G + g]) / np.sqrt(d)
+                p = np.exp(logits - logits.max())
+                p /= p.sum()
+                O[b, h * G + g] = p @ v64
+    return O
+
+
+def offload_gpu_bytes(n_ctx: int, budget: int, d: int, d_dom: int, e: int) -> int:
+    """Per layer and KV head, device-resident cache bytes of the memory-optimised variant
+    (App. C, eq. memory_fasa_m): L*d_dom + b*d_nondom + b*d elements."""
+    return (n_ctx * d_dom + budget * (d - d_dom) + budget * d) * e
+
+
+# ------------------------------------------------------------------------------------
 # the whole decode step: TIP -> TopK-I -> FAC
 # ------------------------------------------------------------------------------------
 def decode_step(q, K, V, fc_idx, n_ctx: int, budget: int, score_dtype=np.float32):

@@ -22,7 +22,8 @@ FASA_BF16, FASA_F32 = 0, 1
 
 EXPORTS = [
     "fasa_workspace_bytes", "fasa_workspace_init", "fasa_validate_fc_idx", "fasa_pack_kcache", "fasa_score", "fasa_topk",
-    "fasa_sparse_attend", "fasa_dense_attend", "fasa_decode_step", "fasa_strerror",
+    "fasa_sparse_attend", "fasa_dense_attend", "fasa_decode_step", "fasa_offload_stage_bytes",
+    "fasa_offload_split_kcache", "fasa_offload_decode_step", "fasa_strerror",
     "fasa_last_hip_error", "fasa_version", "fasa_profile_enable", "fasa_profile_reset",
     "fasa_profile_collect", "fasa_profile_entry",
 ]
@@ -63,6 +64,11 @@ def _load():
     lib.fasa_dense_attend.argtypes = [SP, P, P, P, P, P, SZ, P]; lib.fasa_dense_attend.restype = C.c_int
     lib.fasa_decode_step.argtypes = [SP, P, P, P, P, P, P, P, P, P, P, P, SZ, P]
     lib.fasa_decode_step.restype = C.c_int
+    lib.fasa_offload_stage_bytes.argtypes = [SP]; lib.fasa_offload_stage_bytes.restype = SZ
+    lib.fasa_offload_split_kcache.argtypes = [SP, P, P, P, P, I32, I32, P]
+    lib.fasa_offload_split_kcache.restype = C.c_int
+    lib.fasa_offload_decode_step.argtypes = [SP, P, P, P, P, P, P, P, P, P, P, P, SZ, P, SZ, P]
+    lib.fasa_offload_decode_step.restype = C.c_int
     lib.fasa_strerror.argtypes = [C.c_int]; lib.fasa_strerror.restype = C.c_char_p
     lib.fasa_last_hip_error.argtypes = []; lib.fasa_last_hip_error.restype = C.c_int
     lib.fasa_version.argtypes = []; lib.fasa_version.restype = C.c_int
@@ -154,6 +160,23 @@ def fasa_decode_step(shape, q, K, V, Kp, fc_idx, k_new, v_new, S, T, O, ws, ws_b
     _check(_lib.fasa_decode_step(C.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(Kp), _ptr(fc_idx),
                                  _ptr(k_new), _ptr(v_new), _ptr(S), _ptr(T), _ptr(O), _ptr(ws), ws_bytes,
                                  _stream(stream)), "fasa_decode_step")
+
+
+def fasa_offload_stage_bytes(shape: FasaShape) -> int:
+    return int(_lib.fasa_offload_stage_bytes(C.byref(shape)))
+
+
+def fasa_offload_split_kcache(shape, K, fc_idx, Kp, Knd_host, n_begin: int, n_end: int, stream=None) -> None:
+    _check(_lib.fasa_offload_split_kcache(C.byref(shape), _ptr(K), _ptr(fc_idx), _ptr(Kp), _ptr(Knd_host),
+                                          n_begin, n_end, _stream(stream)), "fasa_offload_split_kcache")
+
+
+def fasa_offload_decode_step(shape, q, Kp, fc_idx, Knd_host, V_host, k_new, v_new, S, T, O, ws, ws_bytes: int,
+                             stage, stage_bytes: int, stream=None) -> None:
+    _check(_lib.fasa_offload_decode_step(C.byref(shape), _ptr(q), _ptr(Kp), _ptr(fc_idx), _ptr(Knd_host),
+                                         _ptr(V_host), _ptr(k_new), _ptr(v_new), _ptr(S), _ptr(T), _ptr(O),
+                                         _ptr(ws), ws_bytes, _ptr(stage), stage_bytes, _stream(stream)),
+           "fasa_offload_decode_step")
 
 
 def fasa_strerror(status: int) -> str:

@@ -276,6 +276,67 @@ int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, v
   return FASA_OK;
 }
 
+size_t fasa_offload_stage_bytes(const fasa_shape* shape) {
+  if (check_shape(shape, kNeedCtx | kNeedBudget) != FASA_OK) return 0;
+  const size_t e = shape->dtype == FASA_BF16 ? 2 : 4;
+  const size_t bsel = (size_t)(shape->budget < shape->n_ctx ? shape->budget : shape->n_ctx);
+  return align256(2 * (size_t)shape->batch * shape->n_kv_heads * bsel * shape->head_dim * e);
+}
+
+int fasa_offload_split_kcache(const fasa_shape* shape, const void* K, const int32_t* fc_idx, void* Kp,
+                              void* Knd_host, int32_t n_begin, int32_t n_end, void* stream) {
+  int rc = check_shape(shape, kNeedFc | kNeedStrides);
+  if (rc != FASA_OK) return rc;
+  if (!K || !fc_idx || !Kp || !Knd_host) return FASA_EINVAL;
+  if (!aligned16(K) || !aligned16(Kp) || !aligned16(fc_idx) || !aligned16(Knd_host)) return FASA_EINVAL;
+  if (n_begin < 0 || n_end < n_begin || n_end > shape->n_cap) return FASA_EINVAL;
+  if (n_begin == n_end) return FASA_OK;
+  FASA_HIP(launch_offload_split(*shape, K, fc_idx, Kp, Knd_host, n_begin, n_end, (hipStream_t)stream));
+  return FASA_OK;
+}
+
+int fasa_offload_decode_step(const fasa_shape* shape, const void* q, void* Kp, const int32_t* fc_idx,
+                             void* Knd_host, void* V_host, const void* k_new, const void* v_new,
+                             float* S, int32_t* T, float* O, void* ws, size_t ws_bytes, void* stage,
+                             size_t stage_bytes, void* stream) {
+  int rc = check_shape(shape, kNeedCtx | kNeedBudget | kNeedFc | kNeedStrides);
+  if (rc != FASA_OK) return rc;
+  if (!q || !Kp || !fc_idx || !Knd_host || !V_host || !S || !T || !O || !stage) return FASA_EINVAL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return FASA_EINVAL;
+  if (!aligned16(q) || !aligned16(Kp) || !aligned16(fc_idx) || !aligned16(Knd_host) || !aligned16(V_host) ||
+      !aligned16(S) || !aligned16(T) || !aligned16(O) || !aligned16(k_new) || !aligned16(v_new) ||
+      !aligned16(stage))
+    return FASA_EINVAL;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc != FASA_OK) return rc;
+  if (stage_bytes < fasa_offload_stage_bytes(shape)) return FASA_EWORKSPACE;
+  const WsLayout w = ws_layout(*shape);
+  char* base = (char*)ws;
+  uint32_t* hist = (uint32_t*)(base + w.hist_off);
+  RowCtl* ctl = (RowCtl*)(base + w.ctl_off);
+  uint2* cand = (uint2*)(base + w.cand_off);
+  hipStream_t st = (hipStream_t)stream;
+  const bool select_all = shape->budget >= shape->n_ctx;
+  const int bsel = shape->budget < shape->n_ctx ? shape->budget : shape->n_ctx;
+  const size_t e = shape->dtype == FASA_BF16 ? 2 : 4;
+  char* KT = (char*)stage;
+  char* VT = KT + (size_t)shape->batch * shape->n_kv_heads * bsel * shape->head_dim * e;
+  if (k_new) FASA_HIP(launch_offload_append(*shape, Kp, Knd_host, V_host, fc_idx, k_new, v_new, st));
+  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, select_all ? nullptr : hist, st));
+  FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st));
+  FASA_HIP(launch_offload_gather(*shape, Kp, Knd_host, V_host, fc_idx, T, KT, VT, st));
+  // exact attention over the rebuilt rows: the staging buffer is a dense cache of bsel tokens
+  fasa_shape ss = *shape;
+  ss.n_ctx = bsel;
+  ss.budget = bsel;
+  ss.kv_stride_n = shape->head_dim;
+  ss.kv_stride_h = (int64_t)bsel * shape->head_dim;
+  ss.kv_stride_b = (int64_t)shape->n_kv_heads * bsel * shape->head_dim;
+  FASA_HIP(launch_attend(ss, true, q, KT, VT, nullptr, O, ctl, (float*)(base + w.part_acc_off),
+                         (float*)(base + w.part_ml_off), st));
+  return FASA_OK;
+}
+
 const char* fasa_strerror(int status) {
   switch (status) {
     case FASA_OK: return "ok";

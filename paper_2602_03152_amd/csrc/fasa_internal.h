@@ -97,4 +97,14 @@ hipError_t launch_attend(const fasa_shape& s, bool dense, const void* q, const v
                          const void* V, const int32_t* T, float* O, RowCtl* ctl, float* part_acc,
                          float* part_ml, hipStream_t st);
 
+// memory-optimised variant (offload.hip)
+hipError_t launch_offload_split(const fasa_shape& s, const void* K, const int32_t* fc_idx, void* Kp,
+                                void* Knd, int n_begin, int n_end, hipStream_t st);
+hipError_t launch_offload_append(const fasa_shape& s, void* Kp, void* Knd, void* Vh,
+                                 const int32_t* fc_idx, const void* k_new, const void* v_new,
+                                 hipStream_t st);
+hipError_t launch_offload_gather(const fasa_shape& s, const void* Kp, const void* Knd, const void* Vh,
+                                 const int32_t* fc_idx, const int32_t* T, void* KT, void* VT,
+                                 hipStream_t st);
+
 }  // namespace fasa
