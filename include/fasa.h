@@ -158,6 +158,27 @@ int fasa_offload_decode_step(const fasa_shape* shape, const void* q, void* Kp, c
                              float* S, int32_t* T, float* O, void* ws, size_t ws_bytes, void* stage,
                              size_t stage_bytes, void* stream);
 
+/* ---- offline calibration (paper Sec. 3.3 eq. ca_k, Sec. 4.1 objective, Alg. 1) ---------------------
+ * Contextual agreement of every single FC with the full head for one query (one calibration
+ * sample):   CA[b,h,i] = | TopK-I(alpha, K) & TopK-I(alpha^(i), K) | / K,
+ * alpha = full-head raw scores, alpha^(i) = scores of FC i alone, both summed over the GQA group of
+ * KV head h, ranked like fasa_topk (ties towards the lower index), K = min(top_k, n_ctx).
+ *   Kp_all  DEVICE [batch][n_kv_heads][head_dim/2][n_cap][2]: fasa_pack_kcache with n_fc = head_dim/2
+ *           and fc_idx[h] = 0, 1, .., head_dim/2 - 1
+ *   CA_sum  DEVICE float [batch][n_kv_heads][head_dim/2]: the call ADDS this sample's CA to it, so a
+ *           loop over samples leaves the sum; divide by the number of samples for the mean
+ *   cws     DEVICE scratch of fasa_calibration_workspace_bytes(); needs no preparation
+ * shape->n_fc and shape->budget are not used.  n_ctx <= 262144 and batch * n_kv_heads * head_dim/2
+ * <= 65535, else FASA_EUNSUPPORTED. */
+size_t fasa_calibration_workspace_bytes(const fasa_shape* shape, int32_t top_k);
+int fasa_contextual_agreement(const fasa_shape* shape, const void* q, const void* Kp_all, int32_t top_k,
+                              float* CA_sum, void* cws, size_t cws_bytes, void* stream);
+
+/* Alg. 1, stage 2 (host-only): fc_idx_host_out[h][0..n_fc) = the n_fc FCs of KV head h with the
+ * largest mean CA, ca_mean_host being HOST float [n_kv_heads][head_dim/2]; equal values go to the
+ * lower FC index; descending order of CA. */
+int fasa_select_dominant_fcs(const fasa_shape* shape, const float* ca_mean_host, int32_t* fc_idx_host_out);
+
 /* Static description of a status code. */
 const char* fasa_strerror(int status);
 /* hipError_t value of the last failed HIP call on this thread (0 if none). */

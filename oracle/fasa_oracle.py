@@ -217,6 +217,36 @@ def offload_gpu_bytes(n_ctx: int, budget: int, d: int, d_dom: int, e: int) -> in
 
 
 # ------------------------------------------------------------------------------------
+# Sec. 3.3 / Alg. 1: contextual agreement of single FCs, offline choice of the dominant set
+# ------------------------------------------------------------------------------------
+def contextual_agreement(q: np.ndarray, K: np.ndarray, n_ctx: int, top_k: int, score_dtype=np.float32) -> np.ndarray:
+    """CA[b,h,i] = | TopK-I(alpha, K) & TopK-I(alpha^(i), K) | / K  (eq. ca_k), alpha = full-head raw
+    scores, alpha^(i) = scores of FC i alone, both summed over the GQA group of KV head h (the same
+    reading as for the online scores) and ranked in `score_dtype` with ties towards the lower index."""
+    Bt, Hq, d = np.asarray(q).shape
+    Hkv = K.shape[1]
+    half = d // 2
+    kk = min(int(top_k), n_ctx)
+    all_fc = np.tile(np.arange(half), (Hkv, 1))
+    S_full, _ = score(q, K, all_fc, n_ctx)
+    T_full = topk(S_full.astype(score_dtype), kk, n_ctx)
+    CA = np.zeros((Bt, Hkv, half))
+    for i in range(half):
+        S_i, _ = score(q, K, np.full((Hkv, 1), i), n_ctx)
+        T_i = topk(S_i.astype(score_dtype), kk, n_ctx)
+        for b in range(Bt):
+            for h in range(Hkv):
+                CA[b, h, i] = len(np.intersect1d(T_full[b, h], T_i[b, h])) / kk
+    return CA
+
+
+def dominant_fcs(ca_mean: np.ndarray, n_fc: int) -> np.ndarray:
+    """I_dom[h] = the n_fc FCs with the largest mean CA (Alg. 1, stage 2); equal values towards the
+    lower FC index; returned in descending order of CA.  ca_mean is [Hkv][d/2]."""
+    return np.stack([np.argsort(-np.asarray(row, dtype=np.float64), kind="stable")[:n_fc] for row in ca_mean]).astype(np.int32)
+
+
+# ------------------------------------------------------------------------------------
 # the whole decode step: TIP -> TopK-I -> FAC
 # ------------------------------------------------------------------------------------
 def decode_step(q, K, V, fc_idx, n_ctx: int, budget: int, score_dtype=np.float32):

@@ -23,7 +23,8 @@ FASA_BF16, FASA_F32 = 0, 1
 EXPORTS = [
     "fasa_workspace_bytes", "fasa_workspace_init", "fasa_validate_fc_idx", "fasa_pack_kcache", "fasa_score", "fasa_topk",
     "fasa_sparse_attend", "fasa_dense_attend", "fasa_decode_step", "fasa_offload_stage_bytes",
-    "fasa_offload_split_kcache", "fasa_offload_decode_step", "fasa_strerror",
+    "fasa_offload_split_kcache", "fasa_offload_decode_step", "fasa_calibration_workspace_bytes",
+    "fasa_contextual_agreement", "fasa_select_dominant_fcs", "fasa_strerror",
     "fasa_last_hip_error", "fasa_version", "fasa_profile_enable", "fasa_profile_reset",
     "fasa_profile_collect", "fasa_profile_entry",
 ]
@@ -69,6 +70,10 @@ def _load():
     lib.fasa_offload_split_kcache.restype = C.c_int
     lib.fasa_offload_decode_step.argtypes = [SP, P, P, P, P, P, P, P, P, P, P, P, SZ, P, SZ, P]
     lib.fasa_offload_decode_step.restype = C.c_int
+    lib.fasa_calibration_workspace_bytes.argtypes = [SP, I32]; lib.fasa_calibration_workspace_bytes.restype = SZ
+    lib.fasa_contextual_agreement.argtypes = [SP, P, P, I32, P, P, SZ, P]
+    lib.fasa_contextual_agreement.restype = C.c_int
+    lib.fasa_select_dominant_fcs.argtypes = [SP, P, P]; lib.fasa_select_dominant_fcs.restype = C.c_int
     lib.fasa_strerror.argtypes = [C.c_int]; lib.fasa_strerror.restype = C.c_char_p
     lib.fasa_last_hip_error.argtypes = []; lib.fasa_last_hip_error.restype = C.c_int
     lib.fasa_version.argtypes = []; lib.fasa_version.restype = C.c_int
@@ -177,6 +182,20 @@ def fasa_offload_decode_step(shape, q, Kp, fc_idx, Knd_host, V_host, k_new, v_ne
                                          _ptr(V_host), _ptr(k_new), _ptr(v_new), _ptr(S), _ptr(T), _ptr(O),
                                          _ptr(ws), ws_bytes, _ptr(stage), stage_bytes, _stream(stream)),
            "fasa_offload_decode_step")
+
+
+def fasa_calibration_workspace_bytes(shape: FasaShape, top_k: int) -> int:
+    return int(_lib.fasa_calibration_workspace_bytes(C.byref(shape), top_k))
+
+
+def fasa_contextual_agreement(shape, q, Kp_all, top_k: int, CA_sum, cws, cws_bytes: int, stream=None) -> None:
+    _check(_lib.fasa_contextual_agreement(C.byref(shape), _ptr(q), _ptr(Kp_all), top_k, _ptr(CA_sum), _ptr(cws),
+                                          cws_bytes, _stream(stream)), "fasa_contextual_agreement")
+
+
+def fasa_select_dominant_fcs(shape, ca_mean_host, fc_idx_host_out) -> None:
+    _check(_lib.fasa_select_dominant_fcs(C.byref(shape), _ptr(ca_mean_host), _ptr(fc_idx_host_out)),
+           "fasa_select_dominant_fcs")
 
 
 def fasa_strerror(status: int) -> str:

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libfasa.so")
-SOURCES = ["api.hip", "pack.hip", "score.hip", "topk.hip", "attend.hip", "offload.hip"]
+SOURCES = ["api.hip", "pack.hip", "score.hip", "topk.hip", "attend.hip", "offload.hip", "calib.hip"]
 
 HIPCC = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
 FLAGS = [

@@ -1,5 +1,6 @@
 // C-ABI entry points: argument validation (no HIP call before it passes), workspace carve-up,
 // stage sequencing on the caller's stream, per-kernel profiler.
+#include <algorithm>
 #include <cstring>
 #include <map>
 #include <string>
@@ -334,6 +335,109 @@ int fasa_offload_decode_step(const fasa_shape* shape, const void* q, void* Kp, c
   ss.kv_stride_b = (int64_t)shape->n_kv_heads * bsel * shape->head_dim;
   FASA_HIP(launch_attend(ss, true, q, KT, VT, nullptr, O, ctl, (float*)(base + w.part_acc_off),
                          (float*)(base + w.part_ml_off), st));
+  return FASA_OK;
+}
+
+// ---- offline calibration -------------------------------------------------------------------------
+namespace {
+struct CalibLayout {
+  fasa_shape full, virt;     // all FCs of the real heads; one FC per virtual head
+  size_t fc_all_off, fc_v_off, q_v_off, s_full_off, t_full_off, s_v_off, t_v_off, ws_full_off, ws_virt_off, total;
+  int kk;
+};
+
+int calib_layout(const fasa_shape* shape, int32_t top_k, CalibLayout* L) {
+  int rc = check_shape(shape, kNeedCtx);
+  if (rc != FASA_OK) return rc;
+  if (top_k < 1) return FASA_EINVAL;
+  const int half = shape->head_dim / 2;
+  if ((long long)shape->batch * shape->n_kv_heads * half > 65535) return FASA_EUNSUPPORTED;
+  if (shape->n_ctx > calib_max_ctx()) return FASA_EUNSUPPORTED;
+  const int kk = top_k < shape->n_ctx ? top_k : shape->n_ctx;
+  L->kk = kk;
+  L->full = *shape;
+  L->full.n_fc = half;
+  L->full.budget = kk;
+  L->virt = *shape;
+  L->virt.n_kv_heads = shape->n_kv_heads * half;
+  L->virt.n_q_heads = shape->n_q_heads * half;
+  L->virt.n_fc = 1;
+  L->virt.budget = kk;
+  const size_t e = shape->dtype == FASA_BF16 ? 2 : 4;
+  const size_t rows = (size_t)shape->batch * shape->n_kv_heads;
+  size_t off = 0;
+  L->fc_all_off = off; off = align256(off + (size_t)shape->n_kv_heads * half * 4);
+  L->fc_v_off = off;   off = align256(off + (size_t)shape->n_kv_heads * half * 4);
+  L->q_v_off = off;    off = align256(off + (size_t)shape->batch * shape->n_q_heads * half * shape->head_dim * e);
+  L->s_full_off = off; off = align256(off + rows * shape->n_cap * 4);
+  L->t_full_off = off; off = align256(off + rows * kk * 4);
+  L->s_v_off = off;    off = align256(off + rows * half * shape->n_cap * 4);
+  L->t_v_off = off;    off = align256(off + rows * half * kk * 4);
+  // the two selection problems get workspaces of their own: their layouts differ, and what one
+  // leaves behind (candidate lists) must never sit where the other expects zeroed counters
+  L->ws_full_off = off; off += ws_layout(L->full).total;
+  L->ws_virt_off = off; off += ws_layout(L->virt).total;
+  L->total = off;
+  return FASA_OK;
+}
+}  // namespace
+
+size_t fasa_calibration_workspace_bytes(const fasa_shape* shape, int32_t top_k) {
+  CalibLayout L;
+  return calib_layout(shape, top_k, &L) == FASA_OK ? L.total : 0;
+}
+
+int fasa_contextual_agreement(const fasa_shape* shape, const void* q, const void* Kp_all, int32_t top_k,
+                              float* CA_sum, void* cws, size_t cws_bytes, void* stream) {
+  CalibLayout L;
+  int rc = calib_layout(shape, top_k, &L);
+  if (rc != FASA_OK) return rc;
+  if (!q || !Kp_all || !CA_sum || !cws) return FASA_EINVAL;
+  if (!aligned16(q) || !aligned16(Kp_all) || !aligned16(CA_sum) || !aligned16(cws)) return FASA_EINVAL;
+  if (cws_bytes < L.total) return FASA_EWORKSPACE;
+  char* base = (char*)cws;
+  int32_t* fc_all = (int32_t*)(base + L.fc_all_off);
+  int32_t* fc_v = (int32_t*)(base + L.fc_v_off);
+  void* q_v = base + L.q_v_off;
+  float* S_full = (float*)(base + L.s_full_off);
+  int32_t* T_full = (int32_t*)(base + L.t_full_off);
+  float* S_v = (float*)(base + L.s_v_off);
+  int32_t* T_v = (int32_t*)(base + L.t_v_off);
+  hipStream_t st = (hipStream_t)stream;
+  const bool all = L.kk >= shape->n_ctx;
+  FASA_HIP(launch_calib_prepare(*shape, q, q_v, fc_all, fc_v, st));
+  const WsLayout wv = ws_layout(L.virt);
+  {  // full-head scores and their top-K set (Alg. 1: "compute full attention scores")
+    char* ws = base + L.ws_full_off;
+    const WsLayout w = ws_layout(L.full);
+    uint32_t* hist = (uint32_t*)(ws + w.hist_off);
+    FASA_HIP(launch_ws_clear(L.full, hist, (RowCtl*)(ws + w.ctl_off), st));
+    FASA_HIP(launch_score(L.full, q, Kp_all, fc_all, S_full, all ? nullptr : hist, st));
+    FASA_HIP(launch_select(L.full, S_full, hist, (RowCtl*)(ws + w.ctl_off), (uint2*)(ws + w.cand_off), T_full, st));
+  }
+  {  // single-FC scores of every FC and their top-K sets, as one virtual multi-head problem
+    char* ws = base + L.ws_virt_off;
+    uint32_t* hist = (uint32_t*)(ws + wv.hist_off);
+    FASA_HIP(launch_ws_clear(L.virt, hist, (RowCtl*)(ws + wv.ctl_off), st));
+    FASA_HIP(launch_score(L.virt, q_v, Kp_all, fc_v, S_v, all ? nullptr : hist, st));
+    FASA_HIP(launch_select(L.virt, S_v, hist, (RowCtl*)(ws + wv.ctl_off), (uint2*)(ws + wv.cand_off), T_v, st));
+  }
+  FASA_HIP(launch_calib_intersect(*shape, T_full, T_v, CA_sum, L.kk, st));
+  return FASA_OK;
+}
+
+int fasa_select_dominant_fcs(const fasa_shape* shape, const float* ca_mean_host, int32_t* fc_idx_host_out) {
+  int rc = check_shape(shape, kNeedFc);
+  if (rc != FASA_OK) return rc;
+  if (!ca_mean_host || !fc_idx_host_out) return FASA_EINVAL;
+  const int half = shape->head_dim / 2;
+  for (int h = 0; h < shape->n_kv_heads; ++h) {
+    std::vector<int> order(half);
+    for (int i = 0; i < half; ++i) order[i] = i;
+    const float* ca = ca_mean_host + (size_t)h * half;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return ca[a] > ca[b]; });
+    for (int f = 0; f < shape->n_fc; ++f) fc_idx_host_out[h * shape->n_fc + f] = order[f];
+  }
   return FASA_OK;
 }
 

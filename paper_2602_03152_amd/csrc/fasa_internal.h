@@ -107,4 +107,11 @@ hipError_t launch_offload_gather(const fasa_shape& s, const void* Kp, const void
                                  const int32_t* fc_idx, const int32_t* T, void* KT, void* VT,
                                  hipStream_t st);
 
+// offline calibration (calib.hip)
+hipError_t launch_calib_prepare(const fasa_shape& s, const void* q, void* q_v, int32_t* fc_all,
+                                int32_t* fc_v, hipStream_t st);
+hipError_t launch_calib_intersect(const fasa_shape& s, const int32_t* T_full, const int32_t* T_v,
+                                  float* CA_sum, int kk, hipStream_t st);
+int calib_max_ctx();
+
 }  // namespace fasa

@@ -25,7 +25,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = _declared()
-    assert len(names) >= 19 and "fasa_decode_step" in names and "fasa_pack_kcache" in names
+    assert len(names) >= 22 and "fasa_decode_step" in names and "fasa_pack_kcache" in names
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -141,3 +141,29 @@ def test_profile_api_without_launches():
     fb.fasa_profile_enable(False)
     buf = C.create_string_buffer(8)
     assert fb.lib.fasa_profile_entry(0, buf, 8, None, None) == fb.FASA_EINVAL
+
+
+def test_select_dominant_fcs_matches_the_oracle_rule():
+    from oracle import fasa_oracle as O
+    rng = np.random.default_rng(0)
+    s = _shape(n_fc=16)
+    ca = np.round(rng.random((8, 64)), 2).astype(np.float32)          # rounding creates ties
+    out = np.zeros((8, 16), dtype=np.int32)
+    fb.fasa_select_dominant_fcs(s, ca, out)
+    np.testing.assert_array_equal(out, O.dominant_fcs(ca, 16))
+    with pytest.raises(fb.FasaError):
+        fb.fasa_select_dominant_fcs(s, None, out)
+
+
+def test_calibration_and_offload_sizes_and_errors():
+    s = _shape()
+    assert fb.fasa_calibration_workspace_bytes(s, 64) > 64 * 8 * 1024 * 4
+    assert fb.fasa_calibration_workspace_bytes(s, 0) == 0
+    assert fb.fasa_calibration_workspace_bytes(_shape(batch=200), 64) == 0      # 200 * 8 * 64 virtual heads
+    assert fb.fasa_offload_stage_bytes(s) == 2 * 8 * 100 * 128 * 2 + (-(2 * 8 * 100 * 128 * 2) % 256)
+    L = fb.lib
+    assert L.fasa_contextual_agreement(C.byref(s), A, A, 64, A, A, 16, None) == fb.FASA_EWORKSPACE
+    assert L.fasa_contextual_agreement(C.byref(s), A, None, 64, A, A, 1 << 40, None) == fb.FASA_EINVAL
+    assert L.fasa_offload_decode_step(C.byref(s), A, A, A, A, A, None, None, A, A, A, A, 1 << 40, A, 16, None) == fb.FASA_EWORKSPACE
+    assert L.fasa_offload_decode_step(C.byref(s), A, A, A, None, A, None, None, A, A, A, A, 1 << 40, A, 1 << 40, None) == fb.FASA_EINVAL
+    assert L.fasa_offload_split_kcache(C.byref(s), A, A, A, A, 5, 4, None) == fb.FASA_EINVAL

@@ -1,0 +1,83 @@
+"""GPU parity of the offline calibration (contextual agreement per FC, dominant-FC choice) against
+the CPU oracle, and the whole method end to end: calibrate -> I_dom -> pack -> decode."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fasa_oracle as O
+from paper_2602_03152_amd import workload as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fb():
+    from paper_2602_03152_amd import binding
+    return binding
+
+
+def _calibrate(fb, w, x, queries, top_k):
+    from tests.gpu_util import to_dev
+    half = w.head_dim // 2
+    n_cap = x["n_cap"]
+    tdt = torch.int16 if w.dtype == "bf16" else torch.float32
+    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, half, w.n_ctx, n_cap, top_k, w.dtype)
+    K = to_dev(x["K"])
+    fc_all = torch.arange(half, dtype=torch.int32, device="cuda").repeat(w.n_kv_heads, 1).contiguous()
+    Kp_all = torch.zeros((w.batch, w.n_kv_heads, half, n_cap, 2), dtype=tdt, device="cuda")
+    fb.fasa_pack_kcache(shape, K, fc_all, Kp_all, 0, w.n_ctx)
+    nbytes = fb.fasa_calibration_workspace_bytes(shape, top_k)
+    cws = torch.full((nbytes,), 0x3C, dtype=torch.uint8, device="cuda")       # needs no preparation
+    ca = torch.zeros((w.batch, w.n_kv_heads, half), dtype=torch.float32, device="cuda")
+    for q in queries:
+        fb.fasa_contextual_agreement(shape, to_dev(q), Kp_all, top_k, ca, cws, nbytes)
+    torch.cuda.synchronize()
+    return ca.cpu().numpy()
+
+
+@pytest.mark.parametrize("name,kw,top_k", [
+    ("bf16_g4", dict(cid=1, n_ctx=1024 + 5, budget=64, n_kv_heads=2, n_q_heads=8), 96),
+    ("f32_g1", dict(cid=0, n_ctx=777, budget=64), 50),
+    ("gqa7", dict(cid=3, batch=2, n_ctx=600, budget=64, n_kv_heads=2, n_q_heads=14), 64),
+    ("k_ge_n", dict(cid=1, n_ctx=100, budget=64, n_kv_heads=1, n_q_heads=4), 500),
+])
+def test_contextual_agreement_matches_oracle(fb, name, kw, top_k):
+    kw = dict(kw); cid = kw.pop("cid")
+    w = W.WORKLOADS[cid].scaled(**kw)
+    x = W.make_inputs(w, n_cap=(w.n_ctx + 63) // 64 * 64)
+    q2 = W.make_append(w, x["fc_idx"], step=1, n_before=w.n_ctx - 1)["q"]
+    print("calibration", name, flush=True)
+    got = _calibrate(fb, w, x, [x["q"], q2], top_k)
+    ref = O.contextual_agreement(x["q"], x["K"], w.n_ctx, top_k) + O.contextual_agreement(q2, x["K"], w.n_ctx, top_k)
+    # the ranking is taken on float32 scores on both sides; a float32 rounding difference between the
+    # two evaluation orders can move a token across the K-th place: at most a few counts of 1/K
+    kk = min(top_k, w.n_ctx)
+    cnt_got, cnt_ref = np.rint(got * kk).astype(int), np.rint(ref * kk).astype(int)     # summed intersection sizes
+    assert np.abs(got * kk - cnt_got).max() < 1e-3
+    assert np.abs(cnt_got - cnt_ref).max() <= 4, int(np.abs(cnt_got - cnt_ref).max())
+    print("  exact counts on %.1f %% of (head, FC) pairs" % (100 * (cnt_got == cnt_ref).mean()), flush=True)
+    assert (cnt_got == cnt_ref).mean() > 0.9
+
+
+def test_calibrate_then_decode_end_to_end(fb):
+    """Alg. 1 then Alg. 2 on the device: the calibrated dominant set equals the planted one, and a
+    decode step with it equals the oracle's step."""
+    from tests.gpu_util import Device, to_host
+    w = W.WORKLOADS[1].scaled(n_ctx=1024, budget=64, n_kv_heads=2, n_q_heads=8, n_fc=8, salient_frac=0.0)
+    x = W.make_inputs(w)
+    queries = [x["q"]] + [W.make_append(w, x["fc_idx"], step=s, n_before=w.n_ctx - 1)["q"] for s in range(1, 4)]
+    ca = _calibrate(fb, w, x, queries, 128)[0] / len(queries)
+    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_fc, w.n_ctx, x["n_cap"], w.budget, w.dtype)
+    fc = np.zeros((w.n_kv_heads, w.n_fc), dtype=np.int32)
+    fb.fasa_select_dominant_fcs(shape, np.ascontiguousarray(ca, dtype=np.float32), fc)
+    fb.fasa_validate_fc_idx(shape, fc)
+    for h in range(w.n_kv_heads):
+        assert sorted(fc[h].tolist()) == sorted(x["fc_idx"][h].tolist())
+    x2 = dict(x); x2["fc_idx"] = fc
+    d = Device(w, x2)
+    d.pack()
+    fb.fasa_decode_step(d.shape, d.q, d.K, d.V, d.Kp, d.fc_idx, None, None, d.S, d.T, d.O, d.ws, d.ws_bytes)
+    torch.cuda.synchronize()
+    S, D, T, out = O.decode_step(x["q"], x["K"], x["V"], fc, w.n_ctx, w.budget)
+    np.testing.assert_array_equal(np.sort(to_host(d.T), -1), O.topk(to_host(d.S)[:, :, :w.n_ctx], w.budget, w.n_ctx))
+    assert np.abs(to_host(d.O) - O.sparse_attend(x["q"], x["K"], x["V"], np.sort(to_host(d.T), -1))).max() <= 2e-3
