@@ -131,6 +131,26 @@ int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, v
                      const int32_t* fc_idx, const void* k_new, const void* v_new, float* S,
                      int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream);
 
+/* fasa_decode_step for a batch whose sequences differ in length (paper Sec. 4.1-4.2 per sequence;
+ * the decode loop of Alg. 2 where t advances every step): the lengths live on the DEVICE, so the
+ * same call - or one captured HIP graph of it - serves every step of a growing, ragged batch.
+ *   n_ctx_seq  DEVICE int32[batch], required: valid tokens of sequence b, clamped by the kernels into
+ *              [1, shape->n_ctx];
+ *   budget_seq DEVICE int32[batch] or NULL: token budget of sequence b, clamped into
+ *              [1, shape->budget]; NULL = shape->budget for all.
+ * shape->n_ctx and shape->budget are UPPER BOUNDS: they size the launches and the workspace, and fix
+ * the row pitch of T at P = min(shape->budget, shape->n_ctx).  For sequence b, with N_b and
+ * B_b = min(budget_b, N_b) after clamping:
+ *   k_new/v_new (if given) go to position N_b - 1; S[b,h,0:N_b] and T[b,h,0:B_b] (at T + (b*Hkv+h)*P)
+ *   are written, entries beyond are left as they were; O[b] attends over exactly those B_b tokens.
+ * The arrays are read by the kernels when they run, not at call time: they must stay valid and
+ * unchanged until the step has finished on the stream.  Needs a prepared workspace and leaves it
+ * prepared.  All other arguments as fasa_decode_step. */
+int fasa_decode_step_ragged(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,
+                            const int32_t* fc_idx, const void* k_new, const void* v_new,
+                            const int32_t* n_ctx_seq, const int32_t* budget_seq, float* S, int32_t* T,
+                            float* O, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- memory-optimised variant (paper Sec. 4.3 and Alg. 2: "FASA-M") -----------------------------
  * Only the dominant key dims (Kp) stay on the device.  The non-dominant key dims and all values
  * live in PINNED HOST memory that the device can address (hipHostMalloc / a pinned torch tensor):

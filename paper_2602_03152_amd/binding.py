@@ -22,7 +22,8 @@ FASA_BF16, FASA_F32 = 0, 1
 
 EXPORTS = [
     "fasa_workspace_bytes", "fasa_workspace_init", "fasa_validate_fc_idx", "fasa_pack_kcache", "fasa_score", "fasa_topk",
-    "fasa_sparse_attend", "fasa_dense_attend", "fasa_decode_step", "fasa_offload_stage_bytes",
+    "fasa_sparse_attend", "fasa_dense_attend", "fasa_decode_step", "fasa_decode_step_ragged",
+    "fasa_offload_stage_bytes",
     "fasa_offload_split_kcache", "fasa_offload_decode_step", "fasa_calibration_workspace_bytes",
     "fasa_contextual_agreement", "fasa_select_dominant_fcs", "fasa_strerror",
     "fasa_last_hip_error", "fasa_version", "fasa_profile_enable", "fasa_profile_reset",
@@ -65,6 +66,8 @@ def _load():
     lib.fasa_dense_attend.argtypes = [SP, P, P, P, P, P, SZ, P]; lib.fasa_dense_attend.restype = C.c_int
     lib.fasa_decode_step.argtypes = [SP, P, P, P, P, P, P, P, P, P, P, P, SZ, P]
     lib.fasa_decode_step.restype = C.c_int
+    lib.fasa_decode_step_ragged.argtypes = [SP, P, P, P, P, P, P, P, P, P, P, P, P, P, SZ, P]
+    lib.fasa_decode_step_ragged.restype = C.c_int
     lib.fasa_offload_stage_bytes.argtypes = [SP]; lib.fasa_offload_stage_bytes.restype = SZ
     lib.fasa_offload_split_kcache.argtypes = [SP, P, P, P, P, I32, I32, P]
     lib.fasa_offload_split_kcache.restype = C.c_int
@@ -165,6 +168,14 @@ def fasa_decode_step(shape, q, K, V, Kp, fc_idx, k_new, v_new, S, T, O, ws, ws_b
     _check(_lib.fasa_decode_step(C.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(Kp), _ptr(fc_idx),
                                  _ptr(k_new), _ptr(v_new), _ptr(S), _ptr(T), _ptr(O), _ptr(ws), ws_bytes,
                                  _stream(stream)), "fasa_decode_step")
+
+
+def fasa_decode_step_ragged(shape, q, K, V, Kp, fc_idx, k_new, v_new, n_ctx_seq, budget_seq, S, T, O, ws,
+                            ws_bytes: int, stream=None) -> None:
+    _check(_lib.fasa_decode_step_ragged(C.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(Kp), _ptr(fc_idx),
+                                        _ptr(k_new), _ptr(v_new), _ptr(n_ctx_seq), _ptr(budget_seq),
+                                        _ptr(S), _ptr(T), _ptr(O), _ptr(ws), ws_bytes, _stream(stream)),
+           "fasa_decode_step_ragged")
 
 
 def fasa_offload_stage_bytes(shape: FasaShape) -> int:

@@ -277,6 +277,37 @@ int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, v
   return FASA_OK;
 }
 
+int fasa_decode_step_ragged(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,
+                            const int32_t* fc_idx, const void* k_new, const void* v_new,
+                            const int32_t* n_ctx_seq, const int32_t* budget_seq, float* S, int32_t* T,
+                            float* O, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(shape, kNeedCtx | kNeedBudget | kNeedFc | kNeedStrides);
+  if (rc != FASA_OK) return rc;
+  if (!q || !K || !V || !Kp || !fc_idx || !S || !T || !O || !n_ctx_seq) return FASA_EINVAL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return FASA_EINVAL;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(Kp) || !aligned16(fc_idx) ||
+      !aligned16(S) || !aligned16(T) || !aligned16(O) || !aligned16(k_new) || !aligned16(v_new))
+    return FASA_EINVAL;
+  if (((uintptr_t)n_ctx_seq & 3u) || ((uintptr_t)budget_seq & 3u)) return FASA_EINVAL;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc != FASA_OK) return rc;
+  const WsLayout w = ws_layout(*shape);
+  char* base = (char*)ws;
+  uint32_t* hist = (uint32_t*)(base + w.hist_off);
+  RowCtl* ctl = (RowCtl*)(base + w.ctl_off);
+  uint2* cand = (uint2*)(base + w.cand_off);
+  hipStream_t st = (hipStream_t)stream;
+  const RaggedLens rl{n_ctx_seq, budget_seq};
+  // the launch sequence never depends on the lengths (they are not known on the host): always the
+  // histogram path, which also covers a sequence whose budget reaches its length
+  if (k_new) FASA_HIP(launch_append(*shape, K, V, Kp, fc_idx, k_new, v_new, st, rl));
+  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, hist, st, rl));
+  FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st, rl));
+  FASA_HIP(launch_attend(*shape, false, q, K, V, T, O, ctl, (float*)(base + w.part_acc_off),
+                         (float*)(base + w.part_ml_off), st, rl));
+  return FASA_OK;
+}
+
 size_t fasa_offload_stage_bytes(const fasa_shape* shape) {
   if (check_shape(shape, kNeedCtx | kNeedBudget) != FASA_OK) return 0;
   const size_t e = shape->dtype == FASA_BF16 ? 2 : 4;

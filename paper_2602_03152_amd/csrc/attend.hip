@@ -136,10 +136,12 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
                                                      RowCtl* __restrict__ ctl,
                                                      float* __restrict__ part_acc,
                                                      float* __restrict__ part_ml, int rows,
-                                                     int n_splits, int Hq, int Hkv, int count,
-                                                     int n_ctx, int tok_per_split, long long sb,
+                                                     int n_splits, int Hq, int Hkv, int count_max,
+                                                     int n_ctx_max, int tok_per_split, long long sb,
                                                      long long sh, long long sn,
-                                                     float scale_log2e) {
+                                                     float scale_log2e,
+                                                     const int32_t* __restrict__ n_ctx_seq,
+                                                     const int32_t* __restrict__ budget_seq) {
   constexpr int D = kHeadDim;
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ float sm_acc[4][G][D];
@@ -154,6 +156,9 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
   const int lane = t & 63, wave = t >> 6;
   const int r = lane >> 4, c = lane & 15;
 
+  // entries of this row: the shape's values, or this sequence's own (never more than the shape's)
+  const int n_ctx = seq_n_ctx(n_ctx_seq, b, n_ctx_max);
+  const int count = DENSE ? n_ctx : seq_bsel(budget_seq, b, n_ctx, count_max);
   const int s0 = split * tok_per_split;
   const int s1 = min(count, s0 + tok_per_split);
 
@@ -175,7 +180,7 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
 
   const ET* Kb = K + b * sb + h * sh + 8 * c;
   const ET* Vb = V + b * sb + h * sh + 8 * c;
-  const int32_t* Trow = DENSE ? nullptr : T + (size_t)row * count;
+  const int32_t* Trow = DENSE ? nullptr : T + (size_t)row * count_max;
 
   for (int j0 = s0 + wave * kAttBatch; j0 < s1; j0 += 4 * kAttBatch) {
     bool valid[kAttU];
@@ -316,10 +321,12 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
                                                           RowCtl* __restrict__ ctl,
                                                           float* __restrict__ part_acc,
                                                           float* __restrict__ part_ml, int rows,
-                                                          int n_splits, int Hq, int Hkv, int count,
-                                                          int n_ctx, int tok_per_split, long long sb,
+                                                          int n_splits, int Hq, int Hkv, int count_max,
+                                                          int n_ctx_max, int tok_per_split, long long sb,
                                                           long long sh, long long sn,
-                                                          float scale_log2e) {
+                                                          float scale_log2e,
+                                                          const int32_t* __restrict__ n_ctx_seq,
+                                                          const int32_t* __restrict__ budget_seq) {
   constexpr int D = kHeadDim;
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ float sm_acc[4][G][D];
@@ -336,6 +343,9 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
   const int lane = t & 63, wave = t >> 6;
   const int lo = lane & 15, hi = lane >> 4;
 
+  // entries of this row: the shape's values, or this sequence's own (never more than the shape's)
+  const int n_ctx = seq_n_ctx(n_ctx_seq, b, n_ctx_max);
+  const int count = DENSE ? n_ctx : seq_bsel(budget_seq, b, n_ctx, count_max);
   const int s0 = split * tok_per_split;
   const int s1 = min(count, s0 + tok_per_split);
 #ifdef FASA_TRACE
@@ -359,7 +369,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
 
   const uint16_t* Kb = K + b * sb + h * sh;
   const uint16_t* Vb = V + b * sb + h * sh + 8 * lo;
-  const int32_t* Trow = DENSE ? nullptr : T + (size_t)row * count;
+  const int32_t* Trow = DENSE ? nullptr : T + (size_t)row * count_max;
 
   for (int j0 = s0 + wave * 16; j0 < s1; j0 += 64) {
     // The scaled logit is rounded once and that rounded value is what the running maximum and the
@@ -525,7 +535,7 @@ template <typename ET, int G>
 static hipError_t launch_attend_g(const fasa_shape& s, bool dense, const AttendPlan& p,
                                   const void* q, const void* K, const void* V, const int32_t* T,
                                   float* O, RowCtl* ctl, float* part_acc, float* part_ml,
-                                  hipStream_t st) {
+                                  hipStream_t st, RaggedLens rl) {
   const int rows = s.batch * s.n_kv_heads;
   dim3 grid(rows * p.n_splits), block(256);
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)s.head_dim);
@@ -535,53 +545,53 @@ static hipError_t launch_attend_g(const fasa_shape& s, bool dense, const AttendP
                     (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, T, O, ctl, part_acc,
                     part_ml, rows, p.n_splits, s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx,
                     p.tok_per_split, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                    (long long)s.kv_stride_n, scale_log2e);
+                    (long long)s.kv_stride_n, scale_log2e, rl.n_ctx, rl.budget);
     return launch("fasa_sparse_attend", attend_mfma_kernel<G, false>, grid, block, st,
                   (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, T, O, ctl, part_acc,
                   part_ml, rows, p.n_splits, s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx,
                   p.tok_per_split, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                  (long long)s.kv_stride_n, scale_log2e);
+                  (long long)s.kv_stride_n, scale_log2e, rl.n_ctx, rl.budget);
   }
   if (dense)
     return launch("fasa_dense_attend", attend_kernel<ET, G, true>, grid, block, st, (const ET*)q,
                   (const ET*)K, (const ET*)V, T, O, ctl, part_acc, part_ml, rows, p.n_splits,
                   s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx, p.tok_per_split,
                   (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n,
-                  scale_log2e);
+                  scale_log2e, rl.n_ctx, rl.budget);
   return launch("fasa_sparse_attend", attend_kernel<ET, G, false>, grid, block, st, (const ET*)q,
                 (const ET*)K, (const ET*)V, T, O, ctl, part_acc, part_ml, rows, p.n_splits,
                 s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx, p.tok_per_split,
                 (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n,
-                scale_log2e);
+                scale_log2e, rl.n_ctx, rl.budget);
 }
 
 template <typename ET>
 static hipError_t launch_attend_t(const fasa_shape& s, bool dense, const AttendPlan& p,
                                   const void* q, const void* K, const void* V, const int32_t* T,
                                   float* O, RowCtl* ctl, float* part_acc, float* part_ml,
-                                  hipStream_t st) {
+                                  hipStream_t st, RaggedLens rl) {
   switch (s.n_q_heads / s.n_kv_heads) {
-    case 1: return launch_attend_g<ET, 1>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
-    case 2: return launch_attend_g<ET, 2>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
-    case 3: return launch_attend_g<ET, 3>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
-    case 4: return launch_attend_g<ET, 4>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
-    case 5: return launch_attend_g<ET, 5>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
-    case 6: return launch_attend_g<ET, 6>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
-    case 7: return launch_attend_g<ET, 7>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
-    case 8: return launch_attend_g<ET, 8>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
+    case 1: return launch_attend_g<ET, 1>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
+    case 2: return launch_attend_g<ET, 2>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
+    case 3: return launch_attend_g<ET, 3>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
+    case 4: return launch_attend_g<ET, 4>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
+    case 5: return launch_attend_g<ET, 5>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
+    case 6: return launch_attend_g<ET, 6>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
+    case 7: return launch_attend_g<ET, 7>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
+    case 8: return launch_attend_g<ET, 8>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
     default: return hipErrorInvalidValue;
   }
 }
 
 hipError_t launch_attend(const fasa_shape& s, bool dense, const void* q, const void* K,
                          const void* V, const int32_t* T, float* O, RowCtl* ctl, float* part_acc,
-                         float* part_ml, hipStream_t st) {
+                         float* part_ml, hipStream_t st, RaggedLens rl) {
   const int rows = s.batch * s.n_kv_heads;
   const int count = dense ? s.n_ctx : (s.budget < s.n_ctx ? s.budget : s.n_ctx);
   const AttendPlan p = plan_attend(rows, count, s.n_q_heads / s.n_kv_heads);
   return s.dtype == FASA_BF16
-             ? launch_attend_t<uint16_t>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st)
-             : launch_attend_t<float>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st);
+             ? launch_attend_t<uint16_t>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl)
+             : launch_attend_t<float>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
 }
 
 }  // namespace fasa

@@ -165,6 +165,15 @@ __device__ __forceinline__ void publish_barrier() {
   __syncthreads();
 }
 
+// per-sequence length and budget (see RaggedLens): clamped into [1, upper bound]
+__device__ __forceinline__ int seq_n_ctx(const int32_t* n_ctx, int b, int upper) {
+  return n_ctx ? min(max(n_ctx[b], 1), upper) : upper;
+}
+__device__ __forceinline__ int seq_bsel(const int32_t* budget, int b, int n, int upper_budget) {
+  const int bud = budget ? min(max(budget[b], 1), upper_budget) : upper_budget;
+  return min(bud, n);
+}
+
 // DPP lane exchanges inside a row of 16 lanes (no LDS traffic)
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float x) {

@@ -33,6 +33,14 @@ struct RowCtl {
 };
 static_assert(sizeof(RowCtl) == 128, "one line per row");
 
+// Optional per-sequence lengths (DEVICE arrays of `batch` entries, or null = the uniform values of
+// the shape).  With them the shape's n_ctx and budget are upper bounds that size the grids, and
+// T's row pitch is min(budget, n_ctx) of the shape.
+struct RaggedLens {
+  const int32_t* n_ctx;
+  const int32_t* budget;
+};
+
 // Workspace carve-up (all offsets 256-byte aligned).
 struct WsLayout {
   size_t hist_off, ctl_off, cand_off, part_acc_off, part_ml_off, total;
@@ -84,18 +92,19 @@ hipError_t launch_pack(const fasa_shape& s, const void* K, const int32_t* fc_idx
                        int n_begin, int n_end, hipStream_t st);
 // hist == nullptr: scores only
 hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
-                        float* S, uint32_t* hist, hipStream_t st);
+                        float* S, uint32_t* hist, hipStream_t st, RaggedLens rl = {nullptr, nullptr});
 // zeroes the histogram and the row counters (workspace initialisation)
 hipError_t launch_ws_clear(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, hipStream_t st);
 // appends the new K/V row (position n_ctx - 1) and its packed FCs
 hipError_t launch_append(const fasa_shape& s, void* K, void* V, void* Kp, const int32_t* fc_idx,
-                         const void* k_new, const void* v_new, hipStream_t st);
+                         const void* k_new, const void* v_new, hipStream_t st,
+                         RaggedLens rl = {nullptr, nullptr});
 hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st);
 hipError_t launch_select(const fasa_shape& s, const float* S, const uint32_t* hist, RowCtl* ctl,
-                         uint2* cand, int32_t* T, hipStream_t st);
+                         uint2* cand, int32_t* T, hipStream_t st, RaggedLens rl = {nullptr, nullptr});
 hipError_t launch_attend(const fasa_shape& s, bool dense, const void* q, const void* K,
                          const void* V, const int32_t* T, float* O, RowCtl* ctl, float* part_acc,
-                         float* part_ml, hipStream_t st);
+                         float* part_ml, hipStream_t st, RaggedLens rl = {nullptr, nullptr});
 
 // memory-optimised variant (offload.hip)
 hipError_t launch_offload_split(const fasa_shape& s, const void* K, const int32_t* fc_idx, void* Kp,

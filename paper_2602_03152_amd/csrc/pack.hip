@@ -62,12 +62,13 @@ __global__ __launch_bounds__(256) void append_kernel(ET* __restrict__ K, ET* __r
                                                      const ET* __restrict__ k_new,
                                                      const ET* __restrict__ v_new, int Hkv, int F,
                                                      int n_cap, int n_ctx, long long sb,
-                                                     long long sh, long long sn) {
+                                                     long long sh, long long sn,
+                                                     const int32_t* __restrict__ n_ctx_seq) {
   constexpr int D = kHeadDim;
   const int row = blockIdx.x;
   const int t = threadIdx.x;
   const int b = row / Hkv, h = row % Hkv;
-  const int n = n_ctx - 1;
+  const int n = seq_n_ctx(n_ctx_seq, b, n_ctx) - 1;
   const ET* ks = k_new + (size_t)row * D;
   const ET* vs = v_new + (size_t)row * D;
   if (t < D) {
@@ -97,18 +98,19 @@ hipError_t launch_pack(const fasa_shape& s, const void* K, const int32_t* fc_idx
 }
 
 hipError_t launch_append(const fasa_shape& s, void* K, void* V, void* Kp, const int32_t* fc_idx,
-                         const void* k_new, const void* v_new, hipStream_t st) {
+                         const void* k_new, const void* v_new, hipStream_t st, RaggedLens rl) {
   const int rows = s.batch * s.n_kv_heads;
   dim3 grid(rows), block(256);
   if (s.dtype == FASA_BF16)
     return launch("fasa_append", append_kernel<uint16_t>, grid, block, st, (uint16_t*)K,
                   (uint16_t*)V, (uint16_t*)Kp, fc_idx, (const uint16_t*)k_new,
                   (const uint16_t*)v_new, s.n_kv_heads, s.n_fc, s.n_cap, s.n_ctx,
-                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n,
+                  rl.n_ctx);
   return launch("fasa_append", append_kernel<float>, grid, block, st, (float*)K, (float*)V,
                 (float*)Kp, fc_idx, (const float*)k_new, (const float*)v_new, s.n_kv_heads, s.n_fc,
                 s.n_cap, s.n_ctx, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                (long long)s.kv_stride_n);
+                (long long)s.kv_stride_n, rl.n_ctx);
 }
 
 }  // namespace fasa

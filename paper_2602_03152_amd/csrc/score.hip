@@ -39,8 +39,8 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
                                                     const int32_t* __restrict__ fc_idx,
                                                     float* __restrict__ S,
                                                     uint32_t* __restrict__ hist, int rows,
-                                                    int nslices, int Hq, int Hkv, int F, int N,
-                                                    int n_cap) {
+                                                    int nslices, int Hq, int Hkv, int F, int N_max,
+                                                    int n_cap, const int32_t* __restrict__ n_ctx_seq) {
   constexpr int D = kHeadDim;
   constexpr int TPT = ScoreTraits<ET>::TPT;
   __shared__ float2 qs[D / 2];
@@ -51,6 +51,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
   const int b = row / Hkv, h = row % Hkv;
   const int G = Hq / Hkv;
   const int t = threadIdx.x;
+  const int N = seq_n_ctx(n_ctx_seq, b, N_max);
   const int n0 = (slice * 256 + t) * TPT;
   const bool active = n0 < N;
   const ET* p = Kp + ((size_t)row * F * n_cap + (active ? n0 : 0)) * 2;
@@ -162,7 +163,8 @@ __global__ __launch_bounds__(256) void hist_kernel(const float* __restrict__ S,
 
 template <typename ET>
 static hipError_t launch_score_t(const fasa_shape& s, const void* q, const void* Kp,
-                                 const int32_t* fc_idx, float* S, uint32_t* hist, hipStream_t st) {
+                                 const int32_t* fc_idx, float* S, uint32_t* hist, hipStream_t st,
+                                 RaggedLens rl) {
   const int rows = s.batch * s.n_kv_heads;
   const int per_block = 256 * ScoreTraits<ET>::TPT;
   const int nslices = (s.n_ctx + per_block - 1) / per_block;
@@ -170,15 +172,16 @@ static hipError_t launch_score_t(const fasa_shape& s, const void* q, const void*
   if (hist)
     return launch("fasa_score_hist", score_kernel<ET, true>, grid, block, st, (const ET*)q,
                   (const ET*)Kp, fc_idx, S, hist, rows, nslices, s.n_q_heads, s.n_kv_heads, s.n_fc,
-                  s.n_ctx, s.n_cap);
+                  s.n_ctx, s.n_cap, rl.n_ctx);
   return launch("fasa_score", score_kernel<ET, false>, grid, block, st, (const ET*)q, (const ET*)Kp,
-                fc_idx, S, hist, rows, nslices, s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap);
+                fc_idx, S, hist, rows, nslices, s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap,
+                rl.n_ctx);
 }
 
 hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
-                        float* S, uint32_t* hist, hipStream_t st) {
-  return s.dtype == FASA_BF16 ? launch_score_t<uint16_t>(s, q, Kp, fc_idx, S, hist, st)
-                              : launch_score_t<float>(s, q, Kp, fc_idx, S, hist, st);
+                        float* S, uint32_t* hist, hipStream_t st, RaggedLens rl) {
+  return s.dtype == FASA_BF16 ? launch_score_t<uint16_t>(s, q, Kp, fc_idx, S, hist, st, rl)
+                              : launch_score_t<float>(s, q, Kp, fc_idx, S, hist, st, rl);
 }
 
 hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st) {

@@ -79,7 +79,9 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
                                                      RowCtl* __restrict__ ctl,
                                                      uint2* __restrict__ cand,
                                                      int32_t* __restrict__ T, int rows, int nslices,
-                                                     int N, int n_cap, int bsel) {
+                                                     int N_max, int n_cap, int budget_max, int t_pitch,
+                                                     int Hkv, const int32_t* __restrict__ n_ctx_seq,
+                                                     const int32_t* __restrict__ budget_seq) {
   __shared__ uint32_t wtot[8];
   __shared__ uint32_t bc[4];
   __shared__ uint32_t thr[3];  // threshold bin, tokens above it, tokens inside it
@@ -89,6 +91,8 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   int row, slice;
   row_slice_of_block(rows, nslices, row, slice);
   const int t = threadIdx.x;
+  const int N = seq_n_ctx(n_ctx_seq, row / Hkv, N_max);
+  const int bsel = seq_bsel(budget_seq, row / Hkv, N, budget_max);
   const float* s = S + (size_t)row * n_cap;
   const int base = slice * kSelTokPerBlock;
 #ifdef FASA_TRACE
@@ -167,7 +171,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   tt[2] = wall_clock64();
 #endif
   uint32_t bw = bc[0] + pw, bcand = bc[1] + pc;
-  int32_t* trow = T + (size_t)row * bsel;
+  int32_t* trow = T + (size_t)row * t_pitch;
   uint2* crow = cand + (size_t)row * n_cap;
 #pragma unroll
   for (int k = 0; k < kSelPerThread; ++k) {
@@ -232,15 +236,18 @@ __global__ __launch_bounds__(256) void ws_clear_kernel(uint4* __restrict__ p, si
 }
 
 hipError_t launch_select(const fasa_shape& s, const float* S, const uint32_t* hist, RowCtl* ctl,
-                         uint2* cand, int32_t* T, hipStream_t st) {
+                         uint2* cand, int32_t* T, hipStream_t st, RaggedLens rl) {
   const int rows = s.batch * s.n_kv_heads;
-  if (s.budget >= s.n_ctx) {
+  const bool ragged = rl.n_ctx != nullptr || rl.budget != nullptr;
+  if (s.budget >= s.n_ctx && !ragged) {
     dim3 grid((s.n_ctx + 255) / 256, rows), block(256);
     return launch("fasa_select_all", select_all_kernel, grid, block, st, T, s.n_ctx);
   }
   const int nslices = (s.n_ctx + kSelTokPerBlock - 1) / kSelTokPerBlock;
+  const int t_pitch = s.budget < s.n_ctx ? s.budget : s.n_ctx;
   return launch("fasa_select", select_kernel, dim3(rows * nslices), dim3(256), st, S,
-                const_cast<uint32_t*>(hist), ctl, cand, T, rows, nslices, s.n_ctx, s.n_cap, s.budget);
+                const_cast<uint32_t*>(hist), ctl, cand, T, rows, nslices, s.n_ctx, s.n_cap, s.budget,
+                t_pitch, s.n_kv_heads, rl.n_ctx, rl.budget);
 }
 
 hipError_t launch_ws_clear(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, hipStream_t st) {

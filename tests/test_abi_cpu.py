@@ -25,7 +25,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = _declared()
-    assert len(names) >= 22 and "fasa_decode_step" in names and "fasa_pack_kcache" in names
+    assert len(names) >= 23 and "fasa_decode_step" in names and "fasa_pack_kcache" in names
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -116,6 +116,11 @@ def test_null_and_misaligned_pointers():
     assert L.fasa_dense_attend(C.byref(s), A, A, None, A, A, 1 << 40, None) == fb.FASA_EINVAL
     # k_new without v_new
     assert L.fasa_decode_step(C.byref(s), A, A, A, A, A, A, None, A, A, A, A, 1 << 40, None) == fb.FASA_EINVAL
+    # ragged step: the length array is required, the budget array optional, both 4-byte aligned
+    assert L.fasa_decode_step_ragged(C.byref(s), A, A, A, A, A, None, None, None, None, A, A, A, A, 1 << 40, None) == fb.FASA_EINVAL
+    assert L.fasa_decode_step_ragged(C.byref(s), A, A, A, A, A, None, None, A + 2, None, A, A, A, A, 1 << 40, None) == fb.FASA_EINVAL
+    assert L.fasa_decode_step_ragged(C.byref(s), A, A, A, A, A, None, None, A, A + 1, A, A, A, A, 1 << 40, None) == fb.FASA_EINVAL
+    assert L.fasa_decode_step_ragged(C.byref(s), A, A, A, A, A, None, None, A, None, A, A, A, A, 0, None) == fb.FASA_EWORKSPACE
 
 
 def test_workspace_too_small():
