@@ -39,87 +39,148 @@ __device__ __forceinline__ float to_f32(float v) { return v; }
 
 // Merges the split partials of one row into O.  Called by the row's last workgroup (all 256
 // threads).  The partials were published by other workgroups with agent-scope stores and are read
-// with agent-scope loads.  Pass 1: per query head the global maximum and the normalised weight of
-// every split, kept in LDS; pass 2: thread (half, dim) sums its half of the splits for all query
-// heads, up to 8 splits' loads in flight, then the two halves meet in LDS.
+// with agent-scope loads, 8 bytes (two head dims) at a time.  One memory round trip: every thread
+// first requests the (max, sum) pairs its wave turns into weights, then ALL the weighted-V partials
+// it will sum (they do not depend on the weights) - a split's partial is C = 64 G columns of two
+// floats; thread t owns column t (and t + 256 when C > 256), or, when C <= 128, column t mod C of
+// every P-th split, the P partitions meeting in LDS at the end.
 template <int G>
 __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
                                             const float* __restrict__ part_ml,
                                             float* __restrict__ O, int row, int b, int h, int Hq,
                                             int n_splits, float* wsm /* [G][kMaxSplitsLds] */,
-                                            float* red /* [G] */, float* half_acc /* [G][D] */) {
+                                            float* red /* [G] */, float* xbuf /* [3][C][2] */) {
   constexpr int D = kHeadDim;
+  constexpr int C = G * (D / 2);
+  constexpr int CPT = (C + 255) / 256;
+  constexpr int P = CPT > 1 ? 1 : (256 / C >= 4 ? 4 : (256 / C >= 2 ? 2 : 1));
+  constexpr int RS = 64 / CPT;          // splits in flight per thread and round
+  constexpr int NG = (G + 3) / 4;
   const int t = threadIdx.x;
-  const size_t rbase = (size_t)row * n_splits * G;
-  const int dim = t & (D - 1), half = t >> 7;
-  const float* pa = part_acc + rbase * D + dim;
-  // the weighted-V partials of the first 16 splits are requested before anything else: they do
-  // not depend on the weights, so one memory round trip covers both passes
-  float x[8][G];
-  auto load_round = [&](int s0) {
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int s = s0 + 2 * u;
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-        x[u][g] = (s < n_splits) ? ld_agent(&pa[((size_t)s * G + g) * D]) : 0.f;
-    }
-  };
-  load_round(half);
-
-  // one wave per query head (round-robin): max, then weights, then their sum
   const int wave = t >> 6, lane = t & 63;
-  for (int g = wave; g < G; g += 4) {
-    float mv[kMaxSplitsLds / 64], lv[kMaxSplitsLds / 64];
-    float mx = kNegBig;
+  const size_t rbase = (size_t)row * n_splits * G;
+#ifdef FASA_TRACE
+  unsigned long long ct[4]; ct[0] = wall_clock64();
+#endif
+
+  // (max, sum) pairs: wave w serves query heads w, w + 4; lane = split (+ 64 i).  Indices are
+  // clamped, not tested: the duplicates are masked below.
+  float2 ml[NG][kMaxSplitsLds / 64];
+#pragma unroll
+  for (int gi = 0; gi < NG; ++gi) {
+    const int g = min(wave + 4 * gi, G - 1);
 #pragma unroll
     for (int i = 0; i < kMaxSplitsLds / 64; ++i) {
-      const int s = lane + 64 * i;
-      mv[i] = kNegBig; lv[i] = 0.f;
-      if (s < n_splits) {
-        const size_t pi = (rbase + (size_t)s * G + g) * 2;
-        mv[i] = ld_agent(&part_ml[pi]);
-        lv[i] = ld_agent(&part_ml[pi + 1]);
+      const int sp = min(lane + 64 * i, n_splits - 1);
+      ml[gi][i] = ld_agent(reinterpret_cast<const float2*>(part_ml) + (rbase + (size_t)sp * G + g));
+    }
+  }
+
+  const int part = CPT > 1 ? 0 : t / C;                 // split partition of this thread
+  const int c0 = CPT > 1 ? t : t % C;
+  const bool owner = CPT > 1 || t < P * C;
+  const float2* pa = reinterpret_cast<const float2*>(part_acc + rbase * D);
+  const int K = (n_splits + P - 1) / P;                 // splits per partition
+  float2 x[RS][CPT];
+  auto load_round = [&](int k0) {
+#pragma unroll
+    for (int u0 = 0; u0 < RS; u0 += 8) {
+      if (k0 + u0 < K) {
+#pragma unroll
+        for (int u = u0; u < u0 + 8; ++u) {
+          const int sp = min(part + P * (k0 + u), n_splits - 1);
+#pragma unroll
+          for (int j = 0; j < CPT; ++j)
+            x[u][j] = ld_agent(pa + (size_t)sp * C + min(c0 + 256 * j, C - 1));
+        }
       }
     }
+  };
+  load_round(0);
+
 #pragma unroll
-    for (int i = 0; i < kMaxSplitsLds / 64; ++i) mx = fmaxf(mx, mv[i]);
+  for (int gi = 0; gi < NG; ++gi) {
+    const int g = wave + 4 * gi;
+    float mx = kNegBig;
+#pragma unroll
+    for (int i = 0; i < kMaxSplitsLds / 64; ++i)
+      mx = (lane + 64 * i < n_splits) ? fmaxf(mx, ml[gi][i].x) : mx;
     mx = wave_max(mx);
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < kMaxSplitsLds / 64; ++i) {
-      const int s = lane + 64 * i;
-      const float wgt = exp2f(mv[i] - mx);
-      if (s < n_splits) wsm[g * kMaxSplitsLds + s] = wgt;
-      sum = fmaf(lv[i], wgt, sum);
+      const int sp = lane + 64 * i;
+      const float wgt = sp < n_splits ? exp2f(ml[gi][i].x - mx) : 0.f;
+      wsm[min(g, G - 1) * kMaxSplitsLds + sp] = wgt;   // waves beyond the group rewrite the last head's own values
+      sum = fmaf(ml[gi][i].y, wgt, sum);
     }
     sum = wave_sum(sum);
-    if (lane == 0) red[g] = 1.0f / sum;
+    if (lane == 0 && g < G) red[g] = 1.0f / sum;
   }
   __syncthreads();
-  float a[G];
+#ifdef FASA_TRACE
+  ct[1] = wall_clock64();
+#endif
+
+  float2 a[CPT];
 #pragma unroll
-  for (int g = 0; g < G; ++g) a[g] = 0.f;
-  for (int s0 = half; s0 < n_splits; s0 += 16) {
-    if (s0 != half) load_round(s0);
+  for (int j = 0; j < CPT; ++j) a[j] = make_float2(0.f, 0.f);
+  for (int k0 = 0; k0 < K; k0 += RS) {
+    if (k0) load_round(k0);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int s = s0 + 2 * u;
-      if (s < n_splits) {
+    for (int u0 = 0; u0 < RS; u0 += 8) {
+      if (k0 + u0 < K) {
+        // straight-line inside a chunk of 8 splits: the weight reads go out together.  A split
+        // beyond the row's count has a finite (re-read) partial and weight 0.
+        float wgt[8][CPT];
 #pragma unroll
-        for (int g = 0; g < G; ++g) a[g] = fmaf(x[u][g], wsm[g * kMaxSplitsLds + s], a[g]);
+        for (int u = 0; u < 8; ++u) {
+          const int sp = part + P * (k0 + u0 + u);
+#pragma unroll
+          for (int j = 0; j < CPT; ++j) {
+            const int c = min(c0 + 256 * j, C - 1);
+            const float w0 = wsm[(c / (D / 2)) * kMaxSplitsLds + min(sp, kMaxSplitsLds - 1)];
+            wgt[u][j] = sp < n_splits ? w0 : 0.f;
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int j = 0; j < CPT; ++j) {
+            a[j].x = fmaf(x[u0 + u][j].x, wgt[u][j], a[j].x);
+            a[j].y = fmaf(x[u0 + u][j].y, wgt[u][j], a[j].y);
+          }
       }
     }
   }
-  if (half == 1) {
+#ifdef FASA_TRACE
+  ct[2] = wall_clock64();
+  if (t == 0 && row == 0) printf("combine: weights %llu acc %llu (x10ns) n_splits %d\n", ct[1]-ct[0], ct[2]-ct[1], n_splits);
+#endif
+  if constexpr (P > 1) {
+    float2* xb = reinterpret_cast<float2*>(xbuf);
+    if (owner && part > 0) xb[(part - 1) * C + c0] = a[0];
+    __syncthreads();
+    if (owner && part == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) half_acc[g * D + dim] = a[g];
+      for (int pp = 1; pp < P; ++pp) {
+        const float2 o = xb[(pp - 1) * C + c0];
+        a[0].x += o.x;
+        a[0].y += o.y;
+      }
+    }
   }
-  __syncthreads();
-  if (half == 0) {
+  if (owner && part == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-      O[((size_t)b * Hq + (size_t)h * G + g) * D + dim] = (a[g] + half_acc[g * D + dim]) * red[g];
+    for (int j = 0; j < CPT; ++j) {
+      const int c = c0 + 256 * j;
+      if (c < C) {
+        const int g = c / (D / 2), d2 = c % (D / 2);
+        const float r = red[g];
+        *reinterpret_cast<float2*>(O + ((size_t)b * Hq + (size_t)h * G + g) * D + 2 * d2) =
+            make_float2(a[j].x * r, a[j].y * r);
+      }
+    }
   }
 }
 

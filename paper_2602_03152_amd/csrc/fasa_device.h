@@ -157,6 +157,11 @@ __device__ __forceinline__ uint2 ld_agent(const uint2* p) {
                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
 }
+__device__ __forceinline__ float2 ld_agent(const float2* p) {
+  const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
+}
 // All of this workgroup's earlier stores are acknowledged; then a block barrier.  After it one
 // thread may bump the ticket that tells another workgroup the data is there.
 __device__ __forceinline__ void publish_barrier() {

@@ -30,10 +30,19 @@ __device__ __forceinline__ void fma_pairs<float>(const uint4& w, float qlo, floa
 constexpr int kScoreFB = 16;  // FC planes in flight per thread
 
 // 1-D grid of rows * nslices workgroups, nslices = ceil(N / (256 * TPT)).  One 16-byte load per
-// thread per FC plane: a wave reads 1 KiB contiguous from each plane, up to 16 independent loads in
-// flight per lane.  The loads are issued before anything else; the query gather and the LDS
-// clearing run under their latency.
-template <typename ET, bool HIST>
+// thread per FC plane: a wave reads 1 KiB contiguous from each plane.  NB > 0: F == 16 * NB and all
+// F plane loads of a thread are in flight at once, issued as straight-line code; NB == 0: any F,
+// 16 planes at a time.
+//
+// Vector loads of a wave return in order, so nothing the K planes do not depend on may queue behind
+// them, and a wait for an earlier load is only cheap if the loads after it are unconditional.  Order
+// of issue, all of it branch-free and by every lane (so that nothing can be moved into a test):
+//   1. this lane's column of the group's query heads (lane t: head dim t mod 128, up to 8 heads)
+//      and one entry of the head's dominant-FC list; neither depends on the other;
+//   2. the K planes (lanes beyond the row's length re-read its first tokens);
+//   3. wait for 1 only: group sum per head dim -> LDS, then lanes < F pick their FC's two
+//      components.  This and the LDS clearing run under the latency of 2.
+template <typename ET, bool HIST, int NB>
 __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
                                                     const ET* __restrict__ Kp,
                                                     const int32_t* __restrict__ fc_idx,
@@ -43,6 +52,9 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
                                                     int n_cap, const int32_t* __restrict__ n_ctx_seq) {
   constexpr int D = kHeadDim;
   constexpr int TPT = ScoreTraits<ET>::TPT;
+  constexpr int NW = NB ? NB * kScoreFB : kScoreFB;
+  __shared__ float qsum[256];      // [t]: sum over the group of q[., t mod 128] (upper half: copies)
+  __shared__ int32_t fcl[256];     // [t]: fc_idx[h][min(t, F - 1)]
   __shared__ float2 qs[D / 2];
   __shared__ uint32_t lh[HIST ? kHistBins : 1];
 
@@ -52,44 +64,59 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
   const int G = Hq / Hkv;
   const int t = threadIdx.x;
   const int N = seq_n_ctx(n_ctx_seq, b, N_max);
+  if (slice * 256 * TPT >= N) return;   // whole workgroup beyond this sequence (ragged batches only)
+
+  // ---- 1 ----
+  const ET* qh = q + ((size_t)b * Hq + (size_t)h * G) * D + (t & (D - 1));
+  ET qcol[kMaxGroup];
+#pragma unroll
+  for (int g = 0; g < kMaxGroup; ++g) qcol[g] = qh[(size_t)min(g, G - 1) * D];   // beyond the group: its last head, not added
+  const int32_t fci = fc_idx[h * F + min(t, F - 1)];
+
+  // ---- 2 ----
   const int n0 = (slice * 256 + t) * TPT;
   const bool active = n0 < N;
   const ET* p = Kp + ((size_t)row * F * n_cap + (active ? n0 : 0)) * 2;
   const size_t plane = (size_t)n_cap * 2;
-
-  uint4 w[kScoreFB];
-  int nf = min(F, kScoreFB);
-  if (active) {
+  uint4 w[NW];
+  int nf = NB ? NW : min(F, kScoreFB);
 #pragma unroll
-    for (int u = 0; u < kScoreFB; ++u)
-      if (u < nf) w[u] = *reinterpret_cast<const uint4*>(p + (size_t)u * plane);
-  }
+  for (int u = 0; u < NW; ++u)
+    if (NB || u < nf) w[u] = *reinterpret_cast<const uint4*>(p + (size_t)u * plane);
 
-  if (t < F) {
-    // group-summed dominant query components: sum_g (q_g . k) = (sum_g q_g) . k
-    const int i = fc_idx[h * F + t];
-    float lo = 0.f, hi = 0.f;
-    for (int g = 0; g < G; ++g) {
-      const ET* qh = q + ((size_t)b * Hq + (size_t)h * G + g) * D;
-      if constexpr (sizeof(ET) == 2) {
-        lo += __uint_as_float((uint32_t)qh[i] << 16);
-        hi += __uint_as_float((uint32_t)qh[i + D / 2] << 16);
-      } else {
-        lo += qh[i];
-        hi += qh[i + D / 2];
-      }
+  // ---- 3 ----  sum_g (q_g . k) = (sum_g q_g) . k, g ascending
+  {
+    float sum = 0.f;
+#pragma unroll
+    for (int g = 0; g < kMaxGroup; ++g) {
+      float a;
+      if constexpr (sizeof(ET) == 2) a = __uint_as_float((uint32_t)qcol[g] << 16);
+      else a = qcol[g];
+      sum += g < G ? a : 0.f;
     }
-    qs[t] = make_float2(lo, hi);
+    qsum[t] = sum;
+    fcl[t] = fci;
   }
   if constexpr (HIST) {
     for (int i = t; i < kHistBins; i += 256) lh[i] = 0;
   }
   __syncthreads();
+  if (t < F) {
+    const int i = fcl[t];
+    qs[t] = make_float2(qsum[i], qsum[i + D / 2]);
+  }
+  __syncthreads();
 
-  if (active) {
-    float acc[TPT];
+  float acc[TPT];
 #pragma unroll
-    for (int k = 0; k < TPT; ++k) acc[k] = 0.f;
+  for (int k = 0; k < TPT; ++k) acc[k] = 0.f;
+  if constexpr (NB > 0) {
+#pragma unroll
+    for (int u = 0; u < NW; ++u) {
+      const float2 qf = qs[u];
+      fma_pairs<ET>(w[u], qf.x, qf.y, acc);
+    }
+  } else {
     for (int f0 = 0;;) {
 #pragma unroll
       for (int u = 0; u < kScoreFB; ++u) {
@@ -105,6 +132,8 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
       for (int u = 0; u < kScoreFB; ++u)
         if (u < nf) w[u] = *reinterpret_cast<const uint4*>(p + (size_t)(f0 + u) * plane);
     }
+  }
+  if (active) {
     float* out = S + (size_t)row * n_cap + n0;
     if (n0 + TPT <= N) {
       if constexpr (TPT == 4) *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
@@ -161,21 +190,35 @@ __global__ __launch_bounds__(256) void hist_kernel(const float* __restrict__ S,
   }
 }
 
-template <typename ET>
-static hipError_t launch_score_t(const fasa_shape& s, const void* q, const void* Kp,
+template <typename ET, bool HIST, int NB>
+static hipError_t launch_score_v(const fasa_shape& s, const void* q, const void* Kp,
                                  const int32_t* fc_idx, float* S, uint32_t* hist, hipStream_t st,
                                  RaggedLens rl) {
   const int rows = s.batch * s.n_kv_heads;
   const int per_block = 256 * ScoreTraits<ET>::TPT;
   const int nslices = (s.n_ctx + per_block - 1) / per_block;
-  dim3 grid(rows * nslices), block(256);
-  if (hist)
-    return launch("fasa_score_hist", score_kernel<ET, true>, grid, block, st, (const ET*)q,
-                  (const ET*)Kp, fc_idx, S, hist, rows, nslices, s.n_q_heads, s.n_kv_heads, s.n_fc,
-                  s.n_ctx, s.n_cap, rl.n_ctx);
-  return launch("fasa_score", score_kernel<ET, false>, grid, block, st, (const ET*)q, (const ET*)Kp,
-                fc_idx, S, hist, rows, nslices, s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap,
-                rl.n_ctx);
+  return launch(HIST ? "fasa_score_hist" : "fasa_score", score_kernel<ET, HIST, NB>, dim3(rows * nslices),
+                dim3(256), st, (const ET*)q, (const ET*)Kp, fc_idx, S, hist, rows, nslices, s.n_q_heads,
+                s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap, rl.n_ctx);
+}
+
+template <typename ET, bool HIST>
+static hipError_t launch_score_h(const fasa_shape& s, const void* q, const void* Kp,
+                                 const int32_t* fc_idx, float* S, uint32_t* hist, hipStream_t st,
+                                 RaggedLens rl) {
+  switch (s.n_fc) {
+    case kScoreFB: return launch_score_v<ET, HIST, 1>(s, q, Kp, fc_idx, S, hist, st, rl);
+    case 2 * kScoreFB: return launch_score_v<ET, HIST, 2>(s, q, Kp, fc_idx, S, hist, st, rl);
+    default: return launch_score_v<ET, HIST, 0>(s, q, Kp, fc_idx, S, hist, st, rl);
+  }
+}
+
+template <typename ET>
+static hipError_t launch_score_t(const fasa_shape& s, const void* q, const void* Kp,
+                                 const int32_t* fc_idx, float* S, uint32_t* hist, hipStream_t st,
+                                 RaggedLens rl) {
+  return hist ? launch_score_h<ET, true>(s, q, Kp, fc_idx, S, hist, st, rl)
+              : launch_score_h<ET, false>(s, q, Kp, fc_idx, S, hist, st, rl);
 }
 
 hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,

@@ -25,20 +25,88 @@ __device__ __forceinline__ unsigned long long cand_composite(uint2 c) {
   return ((unsigned long long)(c.x & ((1u << kKeyLowBits) - 1u)) << 32) | (unsigned long long)(~c.y);
 }
 
+// Block-wide search in a 4096-bin histogram of which thread t holds bins 16t .. 16t+15 in hb[]:
+// the bin b with  (entries in bins above b) < need <= (entries in bins >= b).  All 256 threads
+// call; out[0..2] = b, entries above it, entries inside it (LDS; zero if need exceeds the total,
+// the caller presets them).  Ends with a block barrier.
+__device__ __forceinline__ void find_bin_256x16(const uint32_t* hb, uint32_t need, uint32_t* wtot,
+                                                uint32_t* out) {
+  const int t = threadIdx.x;
+  uint32_t mine = 0;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) mine += hb[j];
+  const uint32_t incl = block256_suffix_sum(mine, wtot);
+  uint32_t cum = incl - mine;
+  if (cum < need && need <= incl) {
+#pragma unroll
+    for (int j = 15; j >= 0; --j) {
+      if (cum < need && cum + hb[j] >= need) {
+        out[0] = (uint32_t)(t * 16 + j);
+        out[1] = cum;
+        out[2] = hb[j];
+      }
+      cum += hb[j];
+    }
+  }
+  __syncthreads();
+}
+
 // Exact selection of the `need` largest composites among cand[0..n).  Whole block participates.
 // SHARED_SRC: the list lives in global memory and was written by other workgroups.
+// dhw: LDS scratch of 4096 counters, or null.  With it the first pass takes the top 12 bits of the
+// composite at once, which for a few hundred candidates almost always isolates the boundary
+// candidate, so that no second pass is needed; without it every pass takes 8 bits.
 template <bool SHARED_SRC, int NT>
 __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* out,
                                    uint32_t* dh /*256*/, uint32_t* wtot /*NT/64*/,
-                                   uint32_t* bc /*4: digit, need, count, out counter*/) {
+                                   uint32_t* bc /*4: digit, need, count, out counter*/,
+                                   uint32_t* dhw = nullptr) {
   const int t = threadIdx.x;
   const uint32_t out_cap = (uint32_t)need;  // never write past the row's share of T
   unsigned long long prefix = 0;
   int shift = 52;            // the composite has 52 significant bits: digits at 44, 36, ..., 4, 0
+#ifdef FASA_TRACE
+  unsigned long long rt[5]; for (int i = 0; i < 5; ++i) rt[i] = wall_clock64();
+  int npass = 0;
+#endif
   if (need < n) {
-    while (shift > 0) {
+    bool done = false;
+    if (NT == 256 && dhw != nullptr) {
+      shift = 40;            // 12-bit digit first, then 8-bit digits at 32, 24, ..., 0
+      for (int i = t; i < kHistBins; i += NT) dhw[i] = 0;
+      if (t == 0) { bc[0] = 0; bc[1] = 0; bc[2] = 0; }
+      __syncthreads();
+      for (int i = t; i < n; i += NT) {
+        const unsigned long long c = cand_composite(SHARED_SRC ? ld_agent(&cand[i]) : cand[i]);
+        atomicAdd(&dhw[(uint32_t)(c >> 40)], 1u);
+      }
+      __syncthreads();
+#ifdef FASA_TRACE
+      rt[1] = wall_clock64();
+#endif
+      uint32_t hb[16];
+      const uint4* hp = reinterpret_cast<const uint4*>(dhw + t * 16);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint4 v = hp[j];
+        hb[4 * j] = v.x; hb[4 * j + 1] = v.y; hb[4 * j + 2] = v.z; hb[4 * j + 3] = v.w;
+      }
+      find_bin_256x16(hb, (uint32_t)need, wtot, bc);
+      prefix = bc[0];
+      const uint32_t in_digit = bc[2];
+      need -= (int)bc[1];
+      done = (uint32_t)need == in_digit;     // everything under this prefix is a winner
+      __syncthreads();                       // bc is rewritten by the passes below
+#ifdef FASA_TRACE
+      rt[2] = wall_clock64();
+#endif
+    }
+    while (!done && shift > 0) {
       const int width = shift >= 8 ? 8 : shift;   // the last digit is the 4 bits left over
       shift -= width;
+#ifdef FASA_TRACE
+      ++npass;
+#endif
       if (t < 256) dh[t] = 0;
       __syncthreads();
       for (int i = t; i < n; i += NT) {
@@ -64,6 +132,9 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
   } else {
     shift = 52;  // take all: (c >> 52) == 0 >= 0
   }
+#ifdef FASA_TRACE
+  rt[3] = wall_clock64();
+#endif
   for (int i = t; i < n; i += NT) {
     const uint2 c = SHARED_SRC ? ld_agent(&cand[i]) : cand[i];
     if ((cand_composite(c) >> shift) >= prefix) {
@@ -71,6 +142,10 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
       if (pos < out_cap) out[pos] = (int32_t)c.y;
     }
   }
+#ifdef FASA_TRACE
+  rt[4] = wall_clock64();
+  if (t == 0 && blockIdx.x < 64) printf("resolve: widehist %llu findbin %llu passes(%d) %llu output %llu (x10ns)\n", rt[1]-rt[0], rt[2]-rt[1], npass, rt[3]-rt[2], rt[4]-rt[3]);
+#endif
 }
 
 // 1-D grid of rows * nslices workgroups, nslices = ceil(N / kSelTokPerBlock)
@@ -124,23 +199,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
       const uint4 x = hp[j];
       hb[4 * j] = x.x; hb[4 * j + 1] = x.y; hb[4 * j + 2] = x.z; hb[4 * j + 3] = x.w;
     }
-    uint32_t mine = 0;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) mine += hb[j];
-    const uint32_t incl = block256_suffix_sum(mine, wtot);
-    uint32_t cum = incl - mine;
-    if (cum < (uint32_t)bsel && (uint32_t)bsel <= incl) {
-#pragma unroll
-      for (int j = 15; j >= 0; --j) {
-        if (cum < (uint32_t)bsel && cum + hb[j] >= (uint32_t)bsel) {
-          thr[0] = (uint32_t)(t * 16 + j);
-          thr[1] = cum;
-          thr[2] = hb[j];
-        }
-        cum += hb[j];
-      }
-    }
-    __syncthreads();
+    find_bin_256x16(hb, (uint32_t)bsel, wtot, thr);   // its first barrier orders the zeroing of thr
   }
   const uint32_t tbin = thr[0];
   const uint32_t n_above = thr[1];
@@ -163,8 +222,11 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   uint32_t pw, pc, tw, tc;
   block256_prefix2(__popc(win), __popc(cnd), wtot, pw, pc, tw, tc);
   if (t == 0) {
-    bc[0] = tw ? atomicAdd(&ctl[row].n_sel, tw) : 0u;
-    bc[1] = tc ? atomicAdd(&ctl[row].n_cand, tc) : 0u;
+    // n_sel and n_cand are adjacent: one 64-bit add reserves both ranges in one round trip
+    const unsigned long long old = atomicAdd(reinterpret_cast<unsigned long long*>(&ctl[row].n_sel),
+                                             (unsigned long long)tw | ((unsigned long long)tc << 32));
+    bc[0] = (uint32_t)old;
+    bc[1] = (uint32_t)(old >> 32);
   }
   __syncthreads();
 #ifdef FASA_TRACE
@@ -206,7 +268,9 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
 #ifdef FASA_TRACE
   tt[4] = wall_clock64();
 #endif
-  if (in_lds) resolve_candidates<false, 256>(lc, n_cand, need, trow + n_above, dh, wtot, bc);
+  // with <= 2048 candidates the upper half of lc is free: 4096 counters for a 12-bit first digit
+  uint32_t* dhw = n_cand <= kCandLds / 2 ? reinterpret_cast<uint32_t*>(lc + kCandLds / 2) : nullptr;
+  if (in_lds) resolve_candidates<false, 256>(lc, n_cand, need, trow + n_above, dh, wtot, bc, dhw);
   else resolve_candidates<true, 256>(crow, n_cand, need, trow + n_above, dh, wtot, bc);
 #ifdef FASA_TRACE
   tt[5] = wall_clock64();
