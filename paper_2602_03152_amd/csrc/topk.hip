@@ -37,16 +37,21 @@ __device__ __forceinline__ void find_bin_256x16(const uint32_t* hb, uint32_t nee
   for (int j = 0; j < 16; ++j) mine += hb[j];
   const uint32_t incl = block256_suffix_sum(mine, wtot);
   uint32_t cum = incl - mine;
-  if (cum < need && need <= incl) {
+  const bool owner = cum < need && need <= incl;   // true for exactly one thread of the block
+  // branch-free scan of the 16 bins from the top; the one hit is kept in registers
+  uint32_t bj = 0, ba = 0, bn = 0;
 #pragma unroll
-    for (int j = 15; j >= 0; --j) {
-      if (cum < need && cum + hb[j] >= need) {
-        out[0] = (uint32_t)(t * 16 + j);
-        out[1] = cum;
-        out[2] = hb[j];
-      }
-      cum += hb[j];
-    }
+  for (int j = 15; j >= 0; --j) {
+    const bool hit = cum < need && cum + hb[j] >= need;
+    bj = hit ? (uint32_t)j : bj;
+    ba = hit ? cum : ba;
+    bn = hit ? hb[j] : bn;
+    cum += hb[j];
+  }
+  if (owner) {
+    out[0] = (uint32_t)(t * 16) + bj;
+    out[1] = ba;
+    out[2] = bn;
   }
   __syncthreads();
 }
