@@ -390,7 +390,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
                                                           const int32_t* __restrict__ budget_seq) {
   constexpr int D = kHeadDim;
   __shared__ float sm_m[4][G], sm_l[4][G];
-  __shared__ float sm_acc[4][G][D];
+  __shared__ __align__(16) float sm_acc[4][4][G][D];   // [wave][16-lane group]: weighted V over the group's rows
   __shared__ float wsm[G * kMaxSplitsLds];
   __shared__ float red[G];
   __shared__ uint32_t ticket;
@@ -533,43 +533,50 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
 #ifdef FASA_TRACE
   tt[1] = wall_clock64();
 #endif
-  // ---- wave totals: sum of weights over the 4 lane groups, weighted V over the 4 row groups ----
+  // ---- workgroup totals.  The four 16-lane groups of a wave hold weighted V sums over different
+  // rows at one common scale (the running maximum is per head, not per group): they go to LDS as
+  // they are, 16 partial sums per output, and the merge below adds them - far fewer instructions
+  // than butterflies over 8 G registers per lane. ----
   l_run = xor32_sum(xor16_sum(l_run));
+  if (hi == 0 && lo < G) { sm_m[wave][lo] = m_run; sm_l[wave][lo] = l_run; }
 #pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int k = 0; k < 8; ++k) acc[g][k] = xor32_sum(xor16_sum(acc[g][k]));
-  if (hi == 0) {
-    if (lo < G) { sm_m[wave][lo] = m_run; sm_l[wave][lo] = l_run; }
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int k = 0; k < 8; ++k) sm_acc[wave][g][8 * lo + k] = acc[g][k];
+  for (int g = 0; g < G; ++g) {
+    float4* dst = reinterpret_cast<float4*>(&sm_acc[wave][hi][g][8 * lo]);
+    dst[0] = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
+    dst[1] = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
   }
   __syncthreads();
 
-  // merge the 4 waves; one (query head, head dim) per thread and pass
+  // merge: thread (query head g, 4 head dims)
   const size_t pbase = ((size_t)row * n_splits + split) * G;
-  for (int i = t; i < G * D; i += 256) {
-    const int g = i / D, dim = i % D;
+  if (t < G * (D / 4)) {
+    const int g = t / (D / 4), d4 = t % (D / 4);
     float mn = sm_m[0][g];
 #pragma unroll
     for (int w = 1; w < 4; ++w) mn = fmaxf(mn, sm_m[w][g]);
-    float ls = 0.f, a = 0.f;
+    float ls = 0.f;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const float sc = exp2f(sm_m[w][g] - mn);
       ls = fmaf(sm_l[w][g], sc, ls);
-      a = fmaf(sm_acc[w][g][dim], sc, a);
+      float4 sw = *reinterpret_cast<const float4*>(&sm_acc[w][0][g][4 * d4]);
+#pragma unroll
+      for (int r = 1; r < 4; ++r) {
+        const float4 x = *reinterpret_cast<const float4*>(&sm_acc[w][r][g][4 * d4]);
+        sw.x += x.x; sw.y += x.y; sw.z += x.z; sw.w += x.w;
+      }
+      a.x = fmaf(sw.x, sc, a.x); a.y = fmaf(sw.y, sc, a.y);
+      a.z = fmaf(sw.z, sc, a.z); a.w = fmaf(sw.w, sc, a.w);
     }
     if (n_splits == 1) {
-      O[((size_t)b * Hq + (size_t)h * G + g) * D + dim] = a / ls;
+      *reinterpret_cast<float4*>(O + ((size_t)b * Hq + (size_t)h * G + g) * D + 4 * d4) =
+          make_float4(a.x / ls, a.y / ls, a.z / ls, a.w / ls);
     } else {
-      st_agent(&part_acc[(pbase + g) * D + dim], a);
-      if (dim == 0) {
-        st_agent(&part_ml[(pbase + g) * 2], mn);
-        st_agent(&part_ml[(pbase + g) * 2 + 1], ls);
-      }
+      float2* pa = reinterpret_cast<float2*>(part_acc + (pbase + g) * D + 4 * d4);
+      st_agent(pa, make_float2(a.x, a.y));
+      st_agent(pa + 1, make_float2(a.z, a.w));
+      if (d4 == 0) st_agent(reinterpret_cast<float2*>(part_ml + (pbase + g) * 2), make_float2(mn, ls));
     }
   }
   if (n_splits == 1) return;
@@ -585,7 +592,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
 #endif
   if (ticket != (uint32_t)n_splits - 1u) return;
   if (t == 0) ctl[row].done_att = 0;
-  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, wsm, red, &sm_acc[0][0][0]);
+  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, wsm, red, &sm_acc[0][0][0][0]);
 #ifdef FASA_TRACE
   tt[4] = wall_clock64();
   if (t == 0 && row == 0) printf("attend last(row0, split %d): tiles %llu merge %llu publish+ticket %llu combine %llu (x10ns)\n", split, tt[1]-tt[0], tt[2]-tt[1], tt[3]-tt[2], tt[4]-tt[3]);

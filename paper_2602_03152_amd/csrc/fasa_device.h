@@ -157,6 +157,11 @@ __device__ __forceinline__ uint2 ld_agent(const uint2* p) {
                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
 }
+__device__ __forceinline__ void st_agent(float2* p, float2 v) {
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p),
+                     ((unsigned long long)__float_as_uint(v.y) << 32) | __float_as_uint(v.x),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ float2 ld_agent(const float2* p) {
   const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
