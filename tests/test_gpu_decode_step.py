@@ -103,6 +103,37 @@ def test_decode_step_reduced(fb, name):
     print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
 
 
+def _random_shapes(n_cases, seed=20260203):
+    """Seeded draw over everything the launch plans branch on: row count (XCD-affine or not), GQA group
+    (every template instance), F (the specialised 16 / 32 and the generic path), list length against the
+    split plan, ragged tails, storage type."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n_cases):
+        G = int(rng.integers(1, 9))
+        hkv = int(rng.choice([1, 2, 3, 4, 8]))
+        batch = int(rng.choice([1, 1, 2, 3, 8 // hkv if hkv <= 8 else 1]))
+        n_fc = int(rng.choice([16, 32, int(rng.integers(1, 65))]))
+        n_ctx = int(rng.choice([int(rng.integers(1, 200)), int(rng.integers(200, 3000)), int(rng.integers(3000, 9000))]))
+        budget = int(rng.choice([1, int(rng.integers(1, n_ctx + 1)), int(rng.integers(1, n_ctx + 1)), max(1, n_ctx // 10),
+                                 max(1, n_ctx // 4), n_ctx, n_ctx + 7]))
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        out.append(dict(batch=max(batch, 1), n_kv_heads=hkv, n_q_heads=hkv * G, n_fc=n_fc, n_ctx=n_ctx, budget=budget,
+                        dtype=dtype))
+    return out
+
+
+@pytest.mark.parametrize("case", range(32))
+def test_decode_step_random_shapes(fb, case):
+    kw = _random_shapes(32)[case]
+    w = W.WORKLOADS[1].scaled(**kw)
+    x = W.make_inputs(w, n_cap=(w.n_ctx + 63) // 64 * 64)
+    print("random shape", case, kw, flush=True)
+    d = run_step(fb, w, x)
+    n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget)
+    print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
+
+
 def test_all_fcs_full_budget_is_dense_attention(fb):
     """F = d/2 and B = N on the device: the fused step equals the oracle's dense attention and the
     device's own dense kernel."""
