@@ -432,38 +432,48 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
   const uint16_t* Vb = V + b * sb + h * sh + 8 * lo;
   const int32_t* Trow = DENSE ? nullptr : T + (size_t)row * count_max;
 
-  for (int j0 = s0 + wave * 16; j0 < s1; j0 += 64) {
+  // ---- tile loop, software-pipelined: while a tile is computed, the next tile's K/V rows and the
+  // indices of the tile after it are in flight.  The loads inside the loop are unconditional
+  // (straight-line code keeps the compiler's wait counts exact: a test around a load would turn
+  // every later wait into a wait for everything); indices beyond the range are clamped into it and
+  // only fetched, the K/V prefetch is issued for real tiles only (the last tile is peeled). ----
+  struct TileIdx { int k; int v[4]; };        // list entries (token numbers) of one tile
+  struct TileKV { uint4 kc[4], vc[4]; };
+  auto load_idx = [&](int j0) {
+    TileIdx r;
+    if constexpr (DENSE) {
+      r.k = min(j0 + lo, s1 - 1);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) r.v[u] = min(j0 + 4 * u + hi, s1 - 1);
+    } else {
+      // a stray index can never become a stray address: entries are clamped to the cache below
+      r.k = Trow[min(j0 + lo, s1 - 1)];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) r.v[u] = Trow[min(j0 + 4 * u + hi, s1 - 1)];
+    }
+    return r;
+  };
+  // gather: one K row per lane column (chunks hi, hi+4, hi+8, hi+12), four V rows per lane group
+  auto load_kv = [&](const TileIdx& ix) {
+    TileKV r;
+    const long long koff = (long long)min(max(ix.k, 0), n_ctx - 1) * sn;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r.kc[i] = *reinterpret_cast<const uint4*>(Kb + koff + 8 * (hi + 4 * i));
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      r.vc[u] = *reinterpret_cast<const uint4*>(Vb + (long long)min(max(ix.v[u], 0), n_ctx - 1) * sn);
+    return r;
+  };
+  auto compute_tile = [&](const TileKV& kv, int j0) {
     // The scaled logit is rounded once and that rounded value is what the running maximum and the
     // exponent see: the scaling is never fused into the subtraction of the maximum (the weight of
     // the maximal row must be exactly 1).  Explicit fmaf calls below are not affected.
 #pragma clang fp contract(off)
-    // ---- gather: one K row per lane column, four V rows per lane group ----
-    long long koff;
-    {
-      const int j = j0 + lo;
-      const int jj = j < s1 ? j : s0;
-      const int tok = DENSE ? jj : min(max(Trow[jj], 0), n_ctx - 1);
-      koff = (long long)tok * sn;
-    }
-    long long voff[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = j0 + 4 * u + hi;
-      const int jj = j < s1 ? j : s0;
-      const int tok = DENSE ? jj : min(max(Trow[jj], 0), n_ctx - 1);
-      voff[u] = (long long)tok * sn;
-    }
-    uint4 kc[4], vc[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) kc[i] = *reinterpret_cast<const uint4*>(Kb + koff + 8 * (hi + 4 * i));
-#pragma unroll
-    for (int u = 0; u < 4; ++u) vc[u] = *reinterpret_cast<const uint4*>(Vb + voff[u]);
-
     // ---- logits of the tile: rows 4hi..4hi+3, query head lo ----
     f32x4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kc[i]), qb[i], c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kv.kc[i]), qb[i], c, 0, 0, 0);
 
     float sv[4];
     bool valid[4];
@@ -519,8 +529,9 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
         pg[4] = p1.x; pg[5] = p1.y; pg[6] = p1.z; pg[7] = p1.w;
       }
       float vf[8];
-      vf[0] = bf16_lo(vc[u].x); vf[1] = bf16_hi(vc[u].x); vf[2] = bf16_lo(vc[u].y); vf[3] = bf16_hi(vc[u].y);
-      vf[4] = bf16_lo(vc[u].z); vf[5] = bf16_hi(vc[u].z); vf[6] = bf16_lo(vc[u].w); vf[7] = bf16_hi(vc[u].w);
+      const uint4 vw = kv.vc[u];
+      vf[0] = bf16_lo(vw.x); vf[1] = bf16_hi(vw.x); vf[2] = bf16_lo(vw.y); vf[3] = bf16_hi(vw.y);
+      vf[4] = bf16_lo(vw.z); vf[5] = bf16_hi(vw.z); vf[6] = bf16_lo(vw.w); vf[7] = bf16_hi(vw.w);
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -528,6 +539,21 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();   // the tile's weights are consumed before the next tile overwrites them
+  };
+
+  const int jw = s0 + wave * 16;               // this wave's tiles start at jw, jw + 64, ...
+  if (jw < s1) {
+    const int n_tiles = (s1 - jw + 63) / 64;
+    TileIdx ix_next = load_idx(jw + 64);
+    TileKV cur = load_kv(load_idx(jw));
+    for (int i = 0; i + 1 < n_tiles; ++i) {
+      const int j0 = jw + 64 * i;
+      const TileKV nxt = load_kv(ix_next);
+      ix_next = load_idx(j0 + 128);
+      compute_tile(cur, j0);
+      cur = nxt;
+    }
+    compute_tile(cur, jw + 64 * (n_tiles - 1));
   }
 
 #ifdef FASA_TRACE
