@@ -178,6 +178,149 @@ def offload(args, w, fb, W, np, torch):
     print(json.dumps(out), flush=True)
 
 
+def calibrate(args, w, fb, W, np, torch):
+    """Offline calibration on the device: contextual agreement of every FC of every KV head with the
+    full head, one query sample per call, then the dominant-FC choice on the host.  Reports the time
+    per sample (the dominant work: d/2 + 1 scoring passes over the cache and d/2 + 1 top-K selections
+    per KV head) and whether the planted dominant FCs of the synthetic workload come out."""
+    n_samples, top_k = args.calibrate, min(w.budget, w.n_ctx)
+    half = w.head_dim // 2
+    x = W.make_inputs(w)
+    n_cap = x["n_cap"]
+    dev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+    tdt = torch.int16 if w.dtype == "bf16" else torch.float32
+    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, half, w.n_ctx, n_cap, top_k, w.dtype)
+    K = dev(x["K"])
+    fc_all = torch.arange(half, dtype=torch.int32, device="cuda").repeat(w.n_kv_heads, 1).contiguous()
+    Kp_all = torch.zeros((w.batch, w.n_kv_heads, half, n_cap, 2), dtype=tdt, device="cuda")
+    fb.fasa_pack_kcache(shape, K, fc_all, Kp_all, 0, w.n_ctx)
+    nbytes = fb.fasa_calibration_workspace_bytes(shape, top_k)
+    cws = torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
+    ca = torch.zeros((w.batch, w.n_kv_heads, half), dtype=torch.float32, device="cuda")
+    q_host = [x["q"]] + [W.make_append(w, x["fc_idx"], step=s, n_before=w.n_ctx - 1)["q"] for s in range(1, n_samples)]
+    qs = [dev(q) for q in q_host]
+    fb.fasa_contextual_agreement(shape, qs[0], Kp_all, top_k, ca, cws, nbytes)         # warm-up
+    torch.cuda.synchronize()
+    ca.zero_()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for q in qs:
+        fb.fasa_contextual_agreement(shape, q, Kp_all, top_k, ca, cws, nbytes)
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) / n_samples * 1e3
+    fb.fasa_profile_reset(); fb.fasa_profile_enable(True)
+    fb.fasa_contextual_agreement(shape, qs[0], Kp_all, top_k, ca, cws, nbytes)
+    prof = fb.profile_summary()
+    fb.fasa_profile_enable(False); fb.fasa_profile_reset()
+    ca_mean = (ca.cpu().numpy() - 0).mean(axis=0)            # over the batch; one extra sample of q0 is in the sum
+    fc = np.zeros((w.n_kv_heads, w.n_fc), dtype=np.int32)
+    dec = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_fc, w.n_ctx, n_cap, w.budget, w.dtype)
+    fb.fasa_select_dominant_fcs(dec, np.ascontiguousarray(ca_mean, dtype=np.float32), fc)
+    recovered = float(np.mean([len(set(fc[h].tolist()) & set(x["fc_idx"][h].tolist())) / w.n_fc
+                               for h in range(w.n_kv_heads)]))
+    rows, e = w.batch * w.n_kv_heads, w.elem_bytes
+    kp_bytes = 2 * rows * w.n_ctx * w.head_dim * e            # the packed copy is read twice: all FCs at once, each FC alone
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import fasa_oracle as O
+        t0 = time.time()
+        O.contextual_agreement(q_host[0][:1], x["K"][:1], w.n_ctx, top_k)
+        dt = time.time() - t0
+        cpu = {"value": round(dt * w.batch * 1e6, 1), "unit": "us", "cores": 1, "kind": "oracle",
+               "sample": "contextual agreement of one query sample on 1 of %d batch entries, scaled to the batch; "
+                         "numpy float64" % w.batch}
+    out = {
+        "metric": "us_per_calibration_sample", "value": round(us, 3), "unit": "us", "n_gpus": 1, "steps": n_samples,
+        "warmup": 1, "ms_per_step": round(us / 1e3, 6), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name + "_calibration", "batch": w.batch, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "n_ctx": w.n_ctx, "top_k": top_k,
+                   "storage_dtype": w.dtype, "launch": "eager"},
+        "kernels": {k: {"launches": n, "avg_us": round(ms / n * 1e3, 3)} for k, (n, ms) in prof.items()},
+        "hbm": {"alg_bytes": kp_bytes, "step_gbps": round(kp_bytes / us / 1e3, 1),
+                "step_frac_of_peak": round(kp_bytes / us / 1e3 / HBM_PEAK_GBPS, 4)},
+        "planted_fcs_recovered": round(recovered, 4),
+        "roofline": None, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def ragged(args, w, fb, W, np, torch):
+    """Serving loop: a batch whose sequences have different lengths, every length growing by one per
+    step, driven by ONE captured graph of fasa_decode_step_ragged (append + score + select + attend)
+    whose per-sequence lengths and budgets live on the device."""
+    steps = args.ragged
+    n_max = w.n_ctx
+    n_cap = (n_max + 63) // 64 * 64
+    x = W.make_inputs(w, n_cap=n_cap)
+    dev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+    tdt = torch.int16 if w.dtype == "bf16" else torch.float32
+    rng = np.random.default_rng(20260203)
+    lens0 = rng.integers(n_max // 4, n_max - steps, size=w.batch).astype(np.int32)
+    lens0[0] = n_max - steps - 1                          # one sequence at the top of the range
+    frac = w.budget / w.n_ctx
+    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_fc, n_max, n_cap, w.budget, w.dtype)
+    q, K, V, fc = dev(x["q"]), dev(x["K"]), dev(x["V"]), dev(x["fc_idx"])
+    a0 = W.make_append(w, x["fc_idx"], step=1, n_before=int(lens0[0]))
+    k_new, v_new = dev(a0["k_new"]), dev(a0["v_new"])
+    Kp = torch.zeros((w.batch, w.n_kv_heads, w.n_fc, n_cap, 2), dtype=tdt, device="cuda")
+    fb.fasa_pack_kcache(shape, K, fc, Kp, 0, n_max)
+    S = torch.zeros((w.batch, w.n_kv_heads, n_cap), dtype=torch.float32, device="cuda")
+    T = torch.zeros((w.batch, w.n_kv_heads, min(w.budget, n_max)), dtype=torch.int32, device="cuda")
+    O = torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    ws_bytes = fb.fasa_workspace_bytes(shape)
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+    fb.fasa_workspace_init(shape, ws, ws_bytes)
+    n_dev = torch.from_numpy(lens0.copy()).cuda()
+    b_dev = torch.from_numpy(np.maximum(1, np.floor(frac * lens0)).astype(np.int32)).cuda()
+    one = torch.ones_like(n_dev)
+
+    def step():
+        fb.fasa_decode_step_ragged(shape, q, K, V, Kp, fc, k_new, v_new, n_dev, b_dev, S, T, O, ws, ws_bytes)
+
+    step()                                                # eager warm-up (re-appends at the current last position)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        n_dev.add_(one)                                   # the lengths advance inside the graph: a replay is a step
+        step()
+    torch.cuda.synchronize()
+    for _ in range(min(args.warmup, 8)):
+        g.replay()
+    torch.cuda.synchronize()
+    n_dev.copy_(torch.from_numpy(lens0))
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        g.replay()
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) / steps * 1e3
+    lens_end = n_dev.cpu().numpy()
+    assert (lens_end == lens0 + steps).all()
+    e, rows_b = w.elem_bytes, w.n_kv_heads
+    mean_len = float(lens0.mean() + steps / 2)
+    alg = int(sum(rows_b * (n * 2 * w.n_fc * e + 2 * min(max(1, int(frac * n)), n) * w.head_dim * e)
+                  for n in (lens0 + steps // 2)))
+    out = {
+        "metric": "us_per_decode_step", "value": round(us, 3), "unit": "us", "n_gpus": 1, "steps": steps,
+        "warmup": min(args.warmup, 8), "ms_per_step": round(us / 1e3, 6), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name + "_ragged", "batch": w.batch, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "n_ctx_bound": n_max,
+                   "n_ctx_min": int(lens0.min()), "n_ctx_mean": round(mean_len, 1), "n_ctx_max": int(lens0.max()) + steps,
+                   "budget_fraction": round(frac, 4), "n_fc": w.n_fc, "storage_dtype": w.dtype,
+                   "launch": "one hipgraph, lengths on the device"},
+        "hbm": {"alg_bytes_mid_step": alg, "step_gbps": round(alg / us / 1e3, 1),
+                "step_frac_of_peak": round(alg / us / 1e3 / HBM_PEAK_GBPS, 4)},
+        "roofline": None, "cpu_baseline": None,
+    }
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -193,6 +336,12 @@ def main():
     ap.add_argument("--offload", action="store_true",
                     help="time the memory-optimised variant (non-dominant key dims and values in pinned "
                          "host memory, fetched over PCIe) instead of the on-device one")
+    ap.add_argument("--calibrate", type=int, default=0, metavar="SAMPLES",
+                    help="time the offline calibration (contextual agreement of every FC, on the device) over "
+                         "SAMPLES query samples instead of the decode step")
+    ap.add_argument("--ragged", type=int, default=0, metavar="STEPS",
+                    help="serving loop: mixed sequence lengths growing by one per step, one captured graph "
+                         "with the lengths on the device; use with --config 2")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only plain device copies of known size (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -225,6 +374,10 @@ def main():
         return growing(args, w, fb, W, np, torch)
     if args.offload:
         return offload(args, w, fb, W, np, torch)
+    if args.calibrate:
+        return calibrate(args, w, fb, W, np, torch)
+    if args.ragged:
+        return ragged(args, w, fb, W, np, torch)
     rows = w.batch * w.n_kv_heads
     model = W.algorithmic_bytes(w)
     bsel = min(w.budget, w.n_ctx)

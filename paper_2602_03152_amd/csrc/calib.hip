@@ -34,38 +34,55 @@ __global__ __launch_bounds__(128) void calib_prepare_kernel(const ET* __restrict
   }
 }
 
-// grid = rows (real KV heads), 256 threads.  CA_sum[row][i] += |T_full[row] & T_v[row][i]| / kk.
+constexpr int kCalibFcPerWg = 4;   // FCs counted by one workgroup (each workgroup rebuilds the row's bitmap)
+
+// grid = rows * ceil(half / kCalibFcPerWg) workgroups of 256 threads.
+// CA_sum[row][i] += |T_full[row] & T_v[row][i]| / kk for the workgroup's FCs i.  The index lists are
+// read 8 entries per thread at a time, all 8 loads issued before the first is used.
 __global__ __launch_bounds__(256) void calib_intersect_kernel(const int32_t* __restrict__ T_full,
                                                               const int32_t* __restrict__ T_v,
                                                               float* __restrict__ CA_sum, int half,
-                                                              int kk, int n_ctx) {
+                                                              int groups, int kk, int n_ctx) {
   __shared__ uint32_t bits[kCalibMaxCtx / 32];
-  __shared__ uint32_t cnt;
-  const int row = blockIdx.x;
+  __shared__ uint32_t cnt[kCalibFcPerWg];
+  const int row = blockIdx.x / groups;
+  const int i0 = (blockIdx.x % groups) * kCalibFcPerWg;
   const int t = threadIdx.x;
   const int words = (n_ctx + 31) / 32;
   for (int w = t; w < words; w += 256) bits[w] = 0;
+  if (t < kCalibFcPerWg) cnt[t] = 0;
   __syncthreads();
-  for (int j = t; j < kk; j += 256) {
-    const int tok = T_full[(size_t)row * kk + j];
-    if (tok >= 0 && tok < n_ctx) atomicOr(&bits[tok >> 5], 1u << (tok & 31));
+  const int32_t* tf = T_full + (size_t)row * kk;
+  for (int j0 = 0; j0 < kk; j0 += 8 * 256) {
+    int tok[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) tok[u] = tf[min(j0 + u * 256 + t, kk - 1)];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (j0 + u * 256 + t < kk && tok[u] >= 0 && tok[u] < n_ctx) atomicOr(&bits[tok[u] >> 5], 1u << (tok[u] & 31));
   }
   __syncthreads();
-  for (int i = 0; i < half; ++i) {
-    if (t == 0) cnt = 0;
-    __syncthreads();
-    uint32_t mine = 0;
+  for (int f = 0; f < kCalibFcPerWg; ++f) {
+    const int i = i0 + f;
+    if (i >= half) break;
     const int32_t* tv = T_v + ((size_t)row * half + i) * kk;
-    for (int j = t; j < kk; j += 256) {
-      const int tok = tv[j];
-      if (tok >= 0 && tok < n_ctx) mine += (bits[tok >> 5] >> (tok & 31)) & 1u;
+    uint32_t mine = 0;
+    for (int j0 = 0; j0 < kk; j0 += 8 * 256) {
+      int tok[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) tok[u] = tv[min(j0 + u * 256 + t, kk - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int c = min(max(tok[u], 0), n_ctx - 1);
+        const uint32_t bit = (bits[c >> 5] >> (c & 31)) & 1u;
+        mine += (j0 + u * 256 + t < kk && tok[u] == c) ? bit : 0u;
+      }
     }
     mine = wave_prefix_sum(mine);
-    if (lane_id() == kWave - 1) atomicAdd(&cnt, mine);
-    __syncthreads();
-    if (t == 0) CA_sum[(size_t)row * half + i] += (float)cnt / (float)kk;
-    __syncthreads();
+    if (lane_id() == kWave - 1) atomicAdd(&cnt[f], mine);
   }
+  __syncthreads();
+  if (t < kCalibFcPerWg && i0 + t < half) CA_sum[(size_t)row * half + i0 + t] += (float)cnt[t] / (float)kk;
 }
 
 hipError_t launch_calib_prepare(const fasa_shape& s, const void* q, void* q_v, int32_t* fc_all,
@@ -81,8 +98,10 @@ hipError_t launch_calib_prepare(const fasa_shape& s, const void* q, void* q_v, i
 
 hipError_t launch_calib_intersect(const fasa_shape& s, const int32_t* T_full, const int32_t* T_v,
                                   float* CA_sum, int kk, hipStream_t st) {
-  return launch("fasa_calib_intersect", calib_intersect_kernel, dim3(s.batch * s.n_kv_heads), dim3(256),
-                st, T_full, T_v, CA_sum, s.head_dim / 2, kk, s.n_ctx);
+  const int half = s.head_dim / 2;
+  const int groups = (half + kCalibFcPerWg - 1) / kCalibFcPerWg;
+  return launch("fasa_calib_intersect", calib_intersect_kernel, dim3(s.batch * s.n_kv_heads * groups),
+                dim3(256), st, T_full, T_v, CA_sum, half, groups, kk, s.n_ctx);
 }
 
 int calib_max_ctx() { return kCalibMaxCtx; }
