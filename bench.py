@@ -472,6 +472,29 @@ def main():
             mode = "hipgraph"
     us_per_step = graph_us if mode == "hipgraph" else eager_us
 
+    # ---------------- pass 1b: distribution of single steps (one event pair per step) ----------------
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K_steps)]
+    for i in range(K_steps):
+        evs[i][0].record(); step(sets[i % R]); evs[i][1].record()
+    torch.cuda.synchronize()
+    per = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
+    step_pct = {"p10": round(float(np.percentile(per, 10)), 3), "p50": round(float(np.percentile(per, 50)), 3),
+                "p90": round(float(np.percentile(per, 90)), 3)}
+
+    # ---------------- measured ceiling: a plain device copy (read + write bytes per second) ----------------
+    cp_src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda")
+    cp_dst = torch.empty_like(cp_src)
+    for _ in range(3):
+        cp_dst.copy_(cp_src)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(10):
+        cp_dst.copy_(cp_src)
+    b.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * cp_src.numel() * 10 / (a.elapsed_time(b) * 1e-3) / 1e9
+    del cp_src, cp_dst
+
     # ---------------- pass 2: per-kernel GPU time ----------------
     fb.fasa_profile_reset()
     fb.fasa_profile_enable(True)
@@ -568,7 +591,11 @@ def main():
                 "step_gbps": round(model["alg"] / us_per_step / 1e3, 1),
                 "step_frac_of_peak": round(model["alg"] / us_per_step / 1e3 / HBM_PEAK_GBPS, 4),
                 "kernel_time_gbps": round(model["alg"] / sum_kernel_us / 1e3, 1),
-                "kernel_time_frac_of_peak": round(model["alg"] / sum_kernel_us / 1e3 / HBM_PEAK_GBPS, 4)},
+                "kernel_time_frac_of_peak": round(model["alg"] / sum_kernel_us / 1e3 / HBM_PEAK_GBPS, 4),
+                # second denominator: what a plain 256 MiB device copy moves (read + write) on this machine
+                "copy_ceiling_gbps": round(copy_gbps, 1),
+                "dominant_kernel_frac_of_copy_ceiling": round(achieved / copy_gbps, 4)},
+        "step_us_percentiles": step_pct,
         "eager_us_per_step": round(eager_us, 3),
         "graph_us_per_step": None if graph_us is None else round(graph_us, 3),
         "sum_kernel_us": round(sum_kernel_us, 3),
