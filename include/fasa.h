@@ -151,6 +151,36 @@ int fasa_decode_step_ragged(const fasa_shape* shape, const void* q, void* K, voi
                             const int32_t* n_ctx_seq, const int32_t* budget_seq, float* S, int32_t* T,
                             float* O, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- paged K/V cache (serving engines that hand out the cache in fixed-size blocks) --------------
+ * The rows of K and V live in one pool of blocks of `page_size` tokens; sequence b's logical block j
+ * (tokens j*page_size .. (j+1)*page_size - 1) is pool block block_table[b*max_blocks + j].  Row (b, h, n):
+ *     K + block_table[b*max_blocks + n / page_size] * kv_stride_b + h * kv_stride_h
+ *       + (n % page_size) * kv_stride_n
+ * i.e. kv_stride_b is the element stride between POOL BLOCKS; any block layout with these three
+ * strides works ([block][token][head][dim], [block][head][token][dim], ...).  V uses the same table
+ * and strides.  The packed copy Kp, S and T stay as described above (logical token numbers).
+ * Table entries outside [0, n_pool_blocks) are clamped into it before use (memory safety only). */
+typedef struct fasa_paging {
+  const int32_t* block_table; /* DEVICE int32 [batch][max_blocks]                                  */
+  int32_t max_blocks;         /* row pitch of block_table; max_blocks * page_size >= tokens touched */
+  int32_t page_size;          /* tokens per block, a power of two                                   */
+  int32_t n_pool_blocks;      /* blocks in the pool; n_pool_blocks * page_size < 2^31               */
+  int32_t reserved;           /* must be 0                                                          */
+} fasa_paging;
+
+/* fasa_pack_kcache reading a paged K (paper Alg. 2, Split + UpdateCache of k^dom, as above). */
+int fasa_pack_kcache_paged(const fasa_shape* shape, const fasa_paging* paging, const void* K,
+                           const int32_t* fc_idx, void* Kp, int32_t n_begin, int32_t n_end, void* stream);
+
+/* fasa_decode_step / fasa_decode_step_ragged on a paged K/V cache (paper Sec. 4.1-4.2, Alg. 2 order).
+ * n_ctx_seq and budget_seq are optional here (both NULL: the uniform values of the shape).  The
+ * selection stage also records the pool slot of every selected token in the workspace, so the
+ * attention stage gathers rows without reading the table again.  T receives logical token numbers. */
+int fasa_decode_step_paged(const fasa_shape* shape, const fasa_paging* paging, const void* q, void* K,
+                           void* V, void* Kp, const int32_t* fc_idx, const void* k_new, const void* v_new,
+                           const int32_t* n_ctx_seq, const int32_t* budget_seq, float* S, int32_t* T,
+                           float* O, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- memory-optimised variant (paper Sec. 4.3 and Alg. 2: "FASA-M") -----------------------------
  * Only the dominant key dims (Kp) stay on the device.  The non-dominant key dims and all values
  * live in PINNED HOST memory that the device can address (hipHostMalloc / a pinned torch tensor):

@@ -23,6 +23,7 @@ FASA_BF16, FASA_F32 = 0, 1
 EXPORTS = [
     "fasa_workspace_bytes", "fasa_workspace_init", "fasa_validate_fc_idx", "fasa_pack_kcache", "fasa_score", "fasa_topk",
     "fasa_sparse_attend", "fasa_dense_attend", "fasa_decode_step", "fasa_decode_step_ragged",
+    "fasa_pack_kcache_paged", "fasa_decode_step_paged",
     "fasa_offload_stage_bytes",
     "fasa_offload_split_kcache", "fasa_offload_decode_step", "fasa_calibration_workspace_bytes",
     "fasa_contextual_agreement", "fasa_select_dominant_fcs", "fasa_strerror",
@@ -38,6 +39,11 @@ class FasaShape(C.Structure):
         ("dtype", C.c_int32), ("reserved", C.c_int32),
         ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_n", C.c_int64),
     ]
+
+
+class FasaPaging(C.Structure):
+    _fields_ = [("block_table", C.c_void_p), ("max_blocks", C.c_int32), ("page_size", C.c_int32),
+                ("n_pool_blocks", C.c_int32), ("reserved", C.c_int32)]
 
 
 class FasaError(RuntimeError):
@@ -68,6 +74,11 @@ def _load():
     lib.fasa_decode_step.restype = C.c_int
     lib.fasa_decode_step_ragged.argtypes = [SP, P, P, P, P, P, P, P, P, P, P, P, P, P, SZ, P]
     lib.fasa_decode_step_ragged.restype = C.c_int
+    PP = C.POINTER(FasaPaging)
+    lib.fasa_pack_kcache_paged.argtypes = [SP, PP, P, P, P, I32, I32, P]
+    lib.fasa_pack_kcache_paged.restype = C.c_int
+    lib.fasa_decode_step_paged.argtypes = [SP, PP, P, P, P, P, P, P, P, P, P, P, P, P, P, SZ, P]
+    lib.fasa_decode_step_paged.restype = C.c_int
     lib.fasa_offload_stage_bytes.argtypes = [SP]; lib.fasa_offload_stage_bytes.restype = SZ
     lib.fasa_offload_split_kcache.argtypes = [SP, P, P, P, P, I32, I32, P]
     lib.fasa_offload_split_kcache.restype = C.c_int
@@ -176,6 +187,24 @@ def fasa_decode_step_ragged(shape, q, K, V, Kp, fc_idx, k_new, v_new, n_ctx_seq,
                                         _ptr(k_new), _ptr(v_new), _ptr(n_ctx_seq), _ptr(budget_seq),
                                         _ptr(S), _ptr(T), _ptr(O), _ptr(ws), ws_bytes, _stream(stream)),
            "fasa_decode_step_ragged")
+
+
+def make_paging(block_table, page_size: int, n_pool_blocks: int) -> FasaPaging:
+    """Paging struct for a DEVICE int32 block table [batch][max_blocks] (the tensor must outlive the call)."""
+    return FasaPaging(_ptr(block_table), int(block_table.shape[1]), int(page_size), int(n_pool_blocks), 0)
+
+
+def fasa_pack_kcache_paged(shape, paging, K, fc_idx, Kp, n_begin: int, n_end: int, stream=None) -> None:
+    _check(_lib.fasa_pack_kcache_paged(C.byref(shape), C.byref(paging), _ptr(K), _ptr(fc_idx), _ptr(Kp), n_begin,
+                                       n_end, _stream(stream)), "fasa_pack_kcache_paged")
+
+
+def fasa_decode_step_paged(shape, paging, q, K, V, Kp, fc_idx, k_new, v_new, n_ctx_seq, budget_seq, S, T, O, ws,
+                           ws_bytes: int, stream=None) -> None:
+    _check(_lib.fasa_decode_step_paged(C.byref(shape), C.byref(paging), _ptr(q), _ptr(K), _ptr(V), _ptr(Kp),
+                                       _ptr(fc_idx), _ptr(k_new), _ptr(v_new), _ptr(n_ctx_seq), _ptr(budget_seq),
+                                       _ptr(S), _ptr(T), _ptr(O), _ptr(ws), ws_bytes, _stream(stream)),
+           "fasa_decode_step_paged")
 
 
 def fasa_offload_stage_bytes(shape: FasaShape) -> int:

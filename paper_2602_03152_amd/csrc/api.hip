@@ -101,6 +101,8 @@ WsLayout ws_layout(const fasa_shape& s) {
   w.cand_off = off;      off = align256(off + (size_t)w.rows * s.n_cap * sizeof(uint2));
   w.part_acc_off = off;  off = align256(off + (size_t)w.rows * w.max_splits * G * kHeadDim * sizeof(float));
   w.part_ml_off = off;   off = align256(off + (size_t)w.rows * w.max_splits * G * 2 * sizeof(float));
+  // pool slots of the selected tokens (paged caches); at the end: earlier offsets do not depend on it
+  w.tslot_off = off;     off = align256(off + (size_t)w.rows * (size_t)bsel * sizeof(int32_t));
   w.total = off;
   return w;
 }
@@ -133,9 +135,25 @@ static int check_shape(const fasa_shape* s, unsigned need) {
   return FASA_OK;
 }
 
-static int check_ws(const fasa_shape* s, const void* ws, size_t ws_bytes) {
+// need_slots: the call uses the slot list of a paged cache (the last region of the workspace)
+static int check_ws(const fasa_shape* s, const void* ws, size_t ws_bytes, bool need_slots = true) {
   if (!ws || !aligned16(ws)) return FASA_EINVAL;
-  if (ws_bytes < ws_layout(*s).total) return FASA_EWORKSPACE;
+  const WsLayout w = ws_layout(*s);
+  if (ws_bytes < (need_slots ? w.total : w.tslot_off)) return FASA_EWORKSPACE;
+  return FASA_OK;
+}
+
+// Paged-cache description -> device view.  The table must cover every token the call can touch.
+static int check_paging(const fasa_paging* p, const fasa_shape* s, PageMap* out) {
+  if (!p || !p->block_table || ((uintptr_t)p->block_table & 3u)) return FASA_EINVAL;
+  if (p->reserved != 0) return FASA_EINVAL;
+  if (p->page_size < 1 || (p->page_size & (p->page_size - 1)) != 0) return FASA_EINVAL;
+  if (p->n_pool_blocks < 1 || p->max_blocks < 1) return FASA_EINVAL;
+  if ((long long)p->max_blocks * p->page_size < s->n_ctx) return FASA_EINVAL;
+  if ((long long)p->n_pool_blocks * p->page_size > 0x7fffffffLL) return FASA_EUNSUPPORTED;
+  int shift = 0;
+  while ((1 << shift) < p->page_size) ++shift;
+  *out = PageMap{p->block_table, p->max_blocks, shift, p->n_pool_blocks};
   return FASA_OK;
 }
 
@@ -230,7 +248,7 @@ static int attend_common(const fasa_shape* shape, bool dense, const void* q, con
     return FASA_EINVAL;
   fasa_shape s = *shape;
   if (dense) s.budget = s.n_ctx;
-  rc = check_ws(&s, ws, ws_bytes);
+  rc = check_ws(&s, ws, ws_bytes, false);
   if (rc != FASA_OK) return rc;
   const WsLayout w = ws_layout(s);
   char* base = (char*)ws;
@@ -305,6 +323,58 @@ int fasa_decode_step_ragged(const fasa_shape* shape, const void* q, void* K, voi
   FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st, rl));
   FASA_HIP(launch_attend(*shape, false, q, K, V, T, O, ctl, (float*)(base + w.part_acc_off),
                          (float*)(base + w.part_ml_off), st, rl));
+  return FASA_OK;
+}
+
+int fasa_pack_kcache_paged(const fasa_shape* shape, const fasa_paging* paging, const void* K,
+                           const int32_t* fc_idx, void* Kp, int32_t n_begin, int32_t n_end, void* stream) {
+  int rc = check_shape(shape, kNeedFc | kNeedStrides);
+  if (rc != FASA_OK) return rc;
+  if (!K || !fc_idx || !Kp || !aligned16(K) || !aligned16(Kp) || !aligned16(fc_idx)) return FASA_EINVAL;
+  if (n_begin < 0 || n_end < n_begin || n_end > shape->n_cap) return FASA_EINVAL;
+  fasa_shape cover = *shape;
+  cover.n_ctx = n_end;                       // the table has to reach the last token packed
+  PageMap pm;
+  rc = check_paging(paging, &cover, &pm);
+  if (rc != FASA_OK) return rc;
+  if (n_begin == n_end) return FASA_OK;
+  FASA_HIP(launch_pack(*shape, K, fc_idx, Kp, n_begin, n_end, (hipStream_t)stream, pm));
+  return FASA_OK;
+}
+
+int fasa_decode_step_paged(const fasa_shape* shape, const fasa_paging* paging, const void* q, void* K,
+                           void* V, void* Kp, const int32_t* fc_idx, const void* k_new, const void* v_new,
+                           const int32_t* n_ctx_seq, const int32_t* budget_seq, float* S, int32_t* T,
+                           float* O, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(shape, kNeedCtx | kNeedBudget | kNeedFc | kNeedStrides);
+  if (rc != FASA_OK) return rc;
+  if (!q || !K || !V || !Kp || !fc_idx || !S || !T || !O) return FASA_EINVAL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return FASA_EINVAL;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(Kp) || !aligned16(fc_idx) ||
+      !aligned16(S) || !aligned16(T) || !aligned16(O) || !aligned16(k_new) || !aligned16(v_new))
+    return FASA_EINVAL;
+  if (((uintptr_t)n_ctx_seq & 3u) || ((uintptr_t)budget_seq & 3u)) return FASA_EINVAL;
+  PageMap pm;
+  rc = check_paging(paging, shape, &pm);
+  if (rc != FASA_OK) return rc;
+  rc = check_ws(shape, ws, ws_bytes);
+  if (rc != FASA_OK) return rc;
+  const WsLayout w = ws_layout(*shape);
+  char* base = (char*)ws;
+  uint32_t* hist = (uint32_t*)(base + w.hist_off);
+  RowCtl* ctl = (RowCtl*)(base + w.ctl_off);
+  uint2* cand = (uint2*)(base + w.cand_off);
+  int32_t* Tslot = (int32_t*)(base + w.tslot_off);
+  hipStream_t st = (hipStream_t)stream;
+  const RaggedLens rl{n_ctx_seq, budget_seq};
+  const bool ragged = n_ctx_seq != nullptr || budget_seq != nullptr;
+  const bool select_all = !ragged && shape->budget >= shape->n_ctx;
+  if (k_new) FASA_HIP(launch_append(*shape, K, V, Kp, fc_idx, k_new, v_new, st, rl, pm));
+  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, select_all ? nullptr : hist, st, rl));
+  FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st, rl, pm, Tslot));
+  // the attention kernel gathers by pool slot: the block table is not read again
+  FASA_HIP(launch_attend(*shape, false, q, K, V, Tslot, O, ctl, (float*)(base + w.part_acc_off),
+                         (float*)(base + w.part_ml_off), st, rl, pm));
   return FASA_OK;
 }
 

@@ -202,7 +202,8 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
                                                      long long sh, long long sn,
                                                      float scale_log2e,
                                                      const int32_t* __restrict__ n_ctx_seq,
-                                                     const int32_t* __restrict__ budget_seq) {
+                                                     const int32_t* __restrict__ budget_seq,
+                                                     PageMap pm) {
   constexpr int D = kHeadDim;
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ float sm_acc[4][G][D];
@@ -239,8 +240,13 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
     for (int k = 0; k < 8; ++k) acc[g][k] = 0.f;
   }
 
-  const ET* Kb = K + b * sb + h * sh + 8 * c;
-  const ET* Vb = V + b * sb + h * sh + 8 * c;
+  // list entries are token numbers, or pool slots of a paged cache (block << shift | offset)
+  const bool paged = pm.table != nullptr;
+  const int pshift = paged ? pm.shift : 31, pmask = paged ? (1 << pm.shift) - 1 : 0x7fffffff;
+  const long long blk_stride = paged ? sb : 0;
+  const int slot_max = paged ? (pm.n_pool << pm.shift) - 1 : n_ctx - 1;
+  const ET* Kb = K + (paged ? 0 : b * sb) + h * sh + 8 * c;
+  const ET* Vb = V + (paged ? 0 : b * sb) + h * sh + 8 * c;
   const int32_t* Trow = DENSE ? nullptr : T + (size_t)row * count_max;
 
   for (int j0 = s0 + wave * kAttBatch; j0 < s1; j0 += 4 * kAttBatch) {
@@ -253,8 +259,8 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
       valid[u] = j < s1;
       const int jj = valid[u] ? j : s0;              // any in-range entry; its weight is zeroed
       // a stray index can never become a stray address: entries are clamped to the cache
-      const int tok = DENSE ? jj : min(max(Trow[jj], 0), n_ctx - 1);
-      off[u] = (long long)tok * sn;
+      const int tok = DENSE ? jj : min(max(Trow[jj], 0), slot_max);
+      off[u] = (long long)(tok >> pshift) * blk_stride + (long long)(tok & pmask) * sn;
     }
 #pragma unroll
     for (int u = 0; u < kAttU; ++u) kv[u].load(Kb + off[u]);
@@ -387,7 +393,8 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
                                                           long long sh, long long sn,
                                                           float scale_log2e,
                                                           const int32_t* __restrict__ n_ctx_seq,
-                                                          const int32_t* __restrict__ budget_seq) {
+                                                          const int32_t* __restrict__ budget_seq,
+                                                          PageMap pm) {
   constexpr int D = kHeadDim;
   __shared__ float sm_m[4][G], sm_l[4][G];
   __shared__ __align__(16) float sm_acc[4][4][G][D];   // [wave][16-lane group]: weighted V over the group's rows
@@ -428,8 +435,13 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
     for (int k = 0; k < 8; ++k) acc[g][k] = 0.f;
   float m_run = kNegBig, l_run = 0.f;   // of query head lo, over this lane's rows of every tile
 
-  const uint16_t* Kb = K + b * sb + h * sh;
-  const uint16_t* Vb = V + b * sb + h * sh + 8 * lo;
+  // list entries are token numbers, or pool slots of a paged cache (block << shift | offset)
+  const bool paged = pm.table != nullptr;
+  const int pshift = paged ? pm.shift : 31, pmask = paged ? (1 << pm.shift) - 1 : 0x7fffffff;
+  const long long blk_stride = paged ? sb : 0;
+  const int slot_max = paged ? (pm.n_pool << pm.shift) - 1 : n_ctx - 1;
+  const uint16_t* Kb = K + (paged ? 0 : b * sb) + h * sh;
+  const uint16_t* Vb = V + (paged ? 0 : b * sb) + h * sh + 8 * lo;
   const int32_t* Trow = DENSE ? nullptr : T + (size_t)row * count_max;
 
   // ---- tile loop, software-pipelined: while a tile is computed, the next tile's K/V rows and the
@@ -456,12 +468,15 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
   // gather: one K row per lane column (chunks hi, hi+4, hi+8, hi+12), four V rows per lane group
   auto load_kv = [&](const TileIdx& ix) {
     TileKV r;
-    const long long koff = (long long)min(max(ix.k, 0), n_ctx - 1) * sn;
+    auto row_off = [&](int e) {
+      const int sl = min(max(e, 0), slot_max);
+      return (long long)(sl >> pshift) * blk_stride + (long long)(sl & pmask) * sn;
+    };
+    const long long koff = row_off(ix.k);
 #pragma unroll
     for (int i = 0; i < 4; ++i) r.kc[i] = *reinterpret_cast<const uint4*>(Kb + koff + 8 * (hi + 4 * i));
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
-      r.vc[u] = *reinterpret_cast<const uint4*>(Vb + (long long)min(max(ix.v[u], 0), n_ctx - 1) * sn);
+    for (int u = 0; u < 4; ++u) r.vc[u] = *reinterpret_cast<const uint4*>(Vb + row_off(ix.v[u]));
     return r;
   };
   auto compute_tile = [&](const TileKV& kv, int j0) {
@@ -629,7 +644,7 @@ template <typename ET, int G>
 static hipError_t launch_attend_g(const fasa_shape& s, bool dense, const AttendPlan& p,
                                   const void* q, const void* K, const void* V, const int32_t* T,
                                   float* O, RowCtl* ctl, float* part_acc, float* part_ml,
-                                  hipStream_t st, RaggedLens rl) {
+                                  hipStream_t st, RaggedLens rl, PageMap pm) {
   const int rows = s.batch * s.n_kv_heads;
   dim3 grid(rows * p.n_splits), block(256);
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)s.head_dim);
@@ -639,53 +654,54 @@ static hipError_t launch_attend_g(const fasa_shape& s, bool dense, const AttendP
                     (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, T, O, ctl, part_acc,
                     part_ml, rows, p.n_splits, s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx,
                     p.tok_per_split, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                    (long long)s.kv_stride_n, scale_log2e, rl.n_ctx, rl.budget);
+                    (long long)s.kv_stride_n, scale_log2e, rl.n_ctx, rl.budget, pm);
     return launch("fasa_sparse_attend", attend_mfma_kernel<G, false>, grid, block, st,
                   (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, T, O, ctl, part_acc,
                   part_ml, rows, p.n_splits, s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx,
                   p.tok_per_split, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                  (long long)s.kv_stride_n, scale_log2e, rl.n_ctx, rl.budget);
+                  (long long)s.kv_stride_n, scale_log2e, rl.n_ctx, rl.budget, pm);
   }
   if (dense)
     return launch("fasa_dense_attend", attend_kernel<ET, G, true>, grid, block, st, (const ET*)q,
                   (const ET*)K, (const ET*)V, T, O, ctl, part_acc, part_ml, rows, p.n_splits,
                   s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx, p.tok_per_split,
                   (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n,
-                  scale_log2e, rl.n_ctx, rl.budget);
+                  scale_log2e, rl.n_ctx, rl.budget, pm);
   return launch("fasa_sparse_attend", attend_kernel<ET, G, false>, grid, block, st, (const ET*)q,
                 (const ET*)K, (const ET*)V, T, O, ctl, part_acc, part_ml, rows, p.n_splits,
                 s.n_q_heads, s.n_kv_heads, p.count, s.n_ctx, p.tok_per_split,
                 (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n,
-                scale_log2e, rl.n_ctx, rl.budget);
+                scale_log2e, rl.n_ctx, rl.budget, pm);
 }
 
 template <typename ET>
 static hipError_t launch_attend_t(const fasa_shape& s, bool dense, const AttendPlan& p,
                                   const void* q, const void* K, const void* V, const int32_t* T,
                                   float* O, RowCtl* ctl, float* part_acc, float* part_ml,
-                                  hipStream_t st, RaggedLens rl) {
+                                  hipStream_t st, RaggedLens rl, PageMap pm) {
   switch (s.n_q_heads / s.n_kv_heads) {
-    case 1: return launch_attend_g<ET, 1>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
-    case 2: return launch_attend_g<ET, 2>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
-    case 3: return launch_attend_g<ET, 3>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
-    case 4: return launch_attend_g<ET, 4>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
-    case 5: return launch_attend_g<ET, 5>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
-    case 6: return launch_attend_g<ET, 6>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
-    case 7: return launch_attend_g<ET, 7>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
-    case 8: return launch_attend_g<ET, 8>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
+    case 1: return launch_attend_g<ET, 1>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl, pm);
+    case 2: return launch_attend_g<ET, 2>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl, pm);
+    case 3: return launch_attend_g<ET, 3>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl, pm);
+    case 4: return launch_attend_g<ET, 4>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl, pm);
+    case 5: return launch_attend_g<ET, 5>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl, pm);
+    case 6: return launch_attend_g<ET, 6>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl, pm);
+    case 7: return launch_attend_g<ET, 7>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl, pm);
+    case 8: return launch_attend_g<ET, 8>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl, pm);
     default: return hipErrorInvalidValue;
   }
 }
 
 hipError_t launch_attend(const fasa_shape& s, bool dense, const void* q, const void* K,
                          const void* V, const int32_t* T, float* O, RowCtl* ctl, float* part_acc,
-                         float* part_ml, hipStream_t st, RaggedLens rl) {
+                         float* part_ml, hipStream_t st, RaggedLens rl, PageMap pm) {
   const int rows = s.batch * s.n_kv_heads;
+  if (dense && pm.table != nullptr) return hipErrorInvalidValue;   // identity lists are token numbers
   const int count = dense ? s.n_ctx : (s.budget < s.n_ctx ? s.budget : s.n_ctx);
   const AttendPlan p = plan_attend(rows, count, s.n_q_heads / s.n_kv_heads);
   return s.dtype == FASA_BF16
-             ? launch_attend_t<uint16_t>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl)
-             : launch_attend_t<float>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl);
+             ? launch_attend_t<uint16_t>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl, pm)
+             : launch_attend_t<float>(s, dense, p, q, K, V, T, O, ctl, part_acc, part_ml, st, rl, pm);
 }
 
 }  // namespace fasa

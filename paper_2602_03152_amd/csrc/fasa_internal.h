@@ -41,9 +41,35 @@ struct RaggedLens {
   const int32_t* budget;
 };
 
+// Paged K/V cache as the kernels see it.  table == nullptr: contiguous cache, row (b, n) at
+// b * kv_stride_b + n * kv_stride_n.  Otherwise row (b, n) lives in pool block
+// table[b * max_blocks + (n >> shift)] at offset (n & (page - 1)); kv_stride_b is then the stride
+// between pool blocks.  Table entries are clamped into [0, n_pool): a stray entry can never become
+// a stray address.
+struct PageMap {
+  const int32_t* table;
+  int max_blocks;
+  int shift;     // log2(tokens per block)
+  int n_pool;    // blocks in the pool
+};
+constexpr PageMap kNoPaging = {nullptr, 0, 0, 0};
+
+// pool slot (block * page + offset) of logical token n of sequence b
+__device__ __forceinline__ int kv_slot(const PageMap& pm, int b, int n) {
+  const int blk = min(max(pm.table[(size_t)b * pm.max_blocks + (n >> pm.shift)], 0), pm.n_pool - 1);
+  return (blk << pm.shift) | (n & ((1 << pm.shift) - 1));
+}
+// element offset of K/V row (b, n), without the head term
+__device__ __forceinline__ long long kv_row_offset(const PageMap& pm, int b, int n, long long sb,
+                                                   long long sn) {
+  if (pm.table == nullptr) return b * sb + (long long)n * sn;
+  const int slot = kv_slot(pm, b, n);
+  return (long long)(slot >> pm.shift) * sb + (long long)(slot & ((1 << pm.shift) - 1)) * sn;
+}
+
 // Workspace carve-up (all offsets 256-byte aligned).
 struct WsLayout {
-  size_t hist_off, ctl_off, cand_off, part_acc_off, part_ml_off, total;
+  size_t hist_off, ctl_off, cand_off, part_acc_off, part_ml_off, tslot_off, total;
   int rows, max_splits;
 };
 
@@ -89,7 +115,7 @@ inline hipError_t launch(const char* name, void (*kernel)(KArgs...), dim3 grid, 
 // validated when these are called
 // ---------------------------------------------------------------------------------------------
 hipError_t launch_pack(const fasa_shape& s, const void* K, const int32_t* fc_idx, void* Kp,
-                       int n_begin, int n_end, hipStream_t st);
+                       int n_begin, int n_end, hipStream_t st, PageMap pm = kNoPaging);
 // hist == nullptr: scores only
 hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
                         float* S, uint32_t* hist, hipStream_t st, RaggedLens rl = {nullptr, nullptr});
@@ -98,13 +124,17 @@ hipError_t launch_ws_clear(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, hip
 // appends the new K/V row (position n_ctx - 1) and its packed FCs
 hipError_t launch_append(const fasa_shape& s, void* K, void* V, void* Kp, const int32_t* fc_idx,
                          const void* k_new, const void* v_new, hipStream_t st,
-                         RaggedLens rl = {nullptr, nullptr});
+                         RaggedLens rl = {nullptr, nullptr}, PageMap pm = kNoPaging);
 hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st);
+// Tslot (paged caches only, else null): receives the pool slot of every entry of T, same layout
 hipError_t launch_select(const fasa_shape& s, const float* S, const uint32_t* hist, RowCtl* ctl,
-                         uint2* cand, int32_t* T, hipStream_t st, RaggedLens rl = {nullptr, nullptr});
+                         uint2* cand, int32_t* T, hipStream_t st, RaggedLens rl = {nullptr, nullptr},
+                         PageMap pm = kNoPaging, int32_t* Tslot = nullptr);
+// paged caches: T holds pool slots (launch_select's Tslot), dense must be false
 hipError_t launch_attend(const fasa_shape& s, bool dense, const void* q, const void* K,
                          const void* V, const int32_t* T, float* O, RowCtl* ctl, float* part_acc,
-                         float* part_ml, hipStream_t st, RaggedLens rl = {nullptr, nullptr});
+                         float* part_ml, hipStream_t st, RaggedLens rl = {nullptr, nullptr},
+                         PageMap pm = kNoPaging);
 
 // memory-optimised variant (offload.hip)
 hipError_t launch_offload_split(const fasa_shape& s, const void* K, const int32_t* fc_idx, void* Kp,

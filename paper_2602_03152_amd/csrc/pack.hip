@@ -17,7 +17,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const ET* __restrict__ K,
                                                    const int32_t* __restrict__ fc_idx,
                                                    ET* __restrict__ Kp, int Hkv, int F, int n_cap,
                                                    int n_begin, int n_end, long long sb,
-                                                   long long sh, long long sn) {
+                                                   long long sh, long long sn, PageMap pm) {
   constexpr int D = kHeadDim;
   constexpr int PITCH = D + 16 / sizeof(ET);  // keeps 16-byte alignment, staggers LDS banks
   __shared__ __align__(16) ET tile[kPackTile][PITCH];
@@ -33,10 +33,10 @@ __global__ __launch_bounds__(256) void pack_kernel(const ET* __restrict__ K,
 
   constexpr int VEC = 16 / sizeof(ET);    // elements per 16-byte load
   constexpr int LPR = D / VEC;            // lanes per row
-  const ET* src = K + b * sb + h * sh;
+  const ET* src = K + h * sh;
   for (int i = t; i < nt * LPR; i += 256) {
     const int r = i / LPR, c = i % LPR;
-    const uint4 v = *reinterpret_cast<const uint4*>(src + (long long)(n0 + r) * sn + c * VEC);
+    const uint4 v = *reinterpret_cast<const uint4*>(src + kv_row_offset(pm, b, n0 + r, sb, sn) + c * VEC);
     *reinterpret_cast<uint4*>(&tile[r][c * VEC]) = v;
   }
   __syncthreads();
@@ -63,7 +63,8 @@ __global__ __launch_bounds__(256) void append_kernel(ET* __restrict__ K, ET* __r
                                                      const ET* __restrict__ v_new, int Hkv, int F,
                                                      int n_cap, int n_ctx, long long sb,
                                                      long long sh, long long sn,
-                                                     const int32_t* __restrict__ n_ctx_seq) {
+                                                     const int32_t* __restrict__ n_ctx_seq,
+                                                     PageMap pm) {
   constexpr int D = kHeadDim;
   const int row = blockIdx.x;
   const int t = threadIdx.x;
@@ -71,10 +72,11 @@ __global__ __launch_bounds__(256) void append_kernel(ET* __restrict__ K, ET* __r
   const int n = seq_n_ctx(n_ctx_seq, b, n_ctx) - 1;
   const ET* ks = k_new + (size_t)row * D;
   const ET* vs = v_new + (size_t)row * D;
+  const long long ro = kv_row_offset(pm, b, n, sb, sn) + h * sh;
   if (t < D) {
-    K[b * sb + h * sh + (long long)n * sn + t] = ks[t];
+    K[ro + t] = ks[t];
   } else {
-    V[b * sb + h * sh + (long long)n * sn + (t - D)] = vs[t - D];
+    V[ro + (t - D)] = vs[t - D];
   }
   if (t < F) {
     const int d0 = fc_idx[h * F + t];
@@ -85,20 +87,21 @@ __global__ __launch_bounds__(256) void append_kernel(ET* __restrict__ K, ET* __r
 }
 
 hipError_t launch_pack(const fasa_shape& s, const void* K, const int32_t* fc_idx, void* Kp,
-                       int n_begin, int n_end, hipStream_t st) {
+                       int n_begin, int n_end, hipStream_t st, PageMap pm) {
   const int rows = s.batch * s.n_kv_heads;
   dim3 grid((n_end - n_begin + kPackTile - 1) / kPackTile, rows), block(256);
   if (s.dtype == FASA_BF16)
     return launch("fasa_pack", pack_kernel<uint16_t>, grid, block, st, (const uint16_t*)K, fc_idx,
                   (uint16_t*)Kp, s.n_kv_heads, s.n_fc, s.n_cap, n_begin, n_end,
-                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n, pm);
   return launch("fasa_pack", pack_kernel<float>, grid, block, st, (const float*)K, fc_idx,
                 (float*)Kp, s.n_kv_heads, s.n_fc, s.n_cap, n_begin, n_end,
-                (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+                (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n, pm);
 }
 
 hipError_t launch_append(const fasa_shape& s, void* K, void* V, void* Kp, const int32_t* fc_idx,
-                         const void* k_new, const void* v_new, hipStream_t st, RaggedLens rl) {
+                         const void* k_new, const void* v_new, hipStream_t st, RaggedLens rl,
+                         PageMap pm) {
   const int rows = s.batch * s.n_kv_heads;
   dim3 grid(rows), block(256);
   if (s.dtype == FASA_BF16)
@@ -106,11 +109,11 @@ hipError_t launch_append(const fasa_shape& s, void* K, void* V, void* Kp, const 
                   (uint16_t*)V, (uint16_t*)Kp, fc_idx, (const uint16_t*)k_new,
                   (const uint16_t*)v_new, s.n_kv_heads, s.n_fc, s.n_cap, s.n_ctx,
                   (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n,
-                  rl.n_ctx);
+                  rl.n_ctx, pm);
   return launch("fasa_append", append_kernel<float>, grid, block, st, (float*)K, (float*)V,
                 (float*)Kp, fc_idx, (const float*)k_new, (const float*)v_new, s.n_kv_heads, s.n_fc,
                 s.n_cap, s.n_ctx, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                (long long)s.kv_stride_n, rl.n_ctx);
+                (long long)s.kv_stride_n, rl.n_ctx, pm);
 }
 
 }  // namespace fasa

@@ -61,11 +61,12 @@ __device__ __forceinline__ void find_bin_256x16(const uint32_t* hb, uint32_t nee
 // dhw: LDS scratch of 4096 counters, or null.  With it the first pass takes the top 12 bits of the
 // composite at once, which for a few hundred candidates almost always isolates the boundary
 // candidate, so that no second pass is needed; without it every pass takes 8 bits.
+// out_slot (paged caches, else null): receives the pool slot of every token written to out.
 template <bool SHARED_SRC, int NT>
 __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* out,
                                    uint32_t* dh /*256*/, uint32_t* wtot /*NT/64*/,
                                    uint32_t* bc /*4: digit, need, count, out counter*/,
-                                   uint32_t* dhw = nullptr) {
+                                   uint32_t* dhw, int32_t* out_slot, const PageMap& pm, int b) {
   const int t = threadIdx.x;
   const uint32_t out_cap = (uint32_t)need;  // never write past the row's share of T
   unsigned long long prefix = 0;
@@ -144,7 +145,10 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
     const uint2 c = SHARED_SRC ? ld_agent(&cand[i]) : cand[i];
     if ((cand_composite(c) >> shift) >= prefix) {
       const uint32_t pos = atomicAdd(&bc[3], 1u);
-      if (pos < out_cap) out[pos] = (int32_t)c.y;
+      if (pos < out_cap) {
+        out[pos] = (int32_t)c.y;
+        if (out_slot) out_slot[pos] = kv_slot(pm, b, (int)c.y);   // paged cache: where the row lives
+      }
     }
   }
 #ifdef FASA_TRACE
@@ -161,7 +165,8 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
                                                      int32_t* __restrict__ T, int rows, int nslices,
                                                      int N_max, int n_cap, int budget_max, int t_pitch,
                                                      int Hkv, const int32_t* __restrict__ n_ctx_seq,
-                                                     const int32_t* __restrict__ budget_seq) {
+                                                     const int32_t* __restrict__ budget_seq, PageMap pm,
+                                                     int32_t* __restrict__ Tslot) {
   __shared__ uint32_t wtot[8];
   __shared__ uint32_t bc[4];
   __shared__ uint32_t thr[3];  // threshold bin, tokens above it, tokens inside it
@@ -239,13 +244,18 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
 #endif
   uint32_t bw = bc[0] + pw, bcand = bc[1] + pc;
   int32_t* trow = T + (size_t)row * t_pitch;
+  int32_t* srow = Tslot ? Tslot + (size_t)row * t_pitch : nullptr;
   uint2* crow = cand + (size_t)row * n_cap;
 #pragma unroll
   for (int k = 0; k < kSelPerThread; ++k) {
     const int n = base + ((k >> 2) * 256 + t) * 4 + (k & 3);
     // the bounds hold by construction of the histogram; they are re-checked so that a
     // histogram that does not match S can never turn into an out-of-range store
-    if ((win & (1u << k)) && bw < (uint32_t)bsel) trow[bw++] = n;
+    if ((win & (1u << k)) && bw < (uint32_t)bsel) {
+      trow[bw] = n;
+      if (srow) srow[bw] = kv_slot(pm, row / Hkv, n);
+      ++bw;
+    }
     // candidates are read by the row's last workgroup: published with agent-scope stores
     if ((cnd & (1u << k)) && bcand < (uint32_t)n_cap) st_agent(&crow[bcand++], make_uint2(key[k], (uint32_t)n));
   }
@@ -275,8 +285,9 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
 #endif
   // with <= 2048 candidates the upper half of lc is free: 4096 counters for a 12-bit first digit
   uint32_t* dhw = n_cand <= kCandLds / 2 ? reinterpret_cast<uint32_t*>(lc + kCandLds / 2) : nullptr;
-  if (in_lds) resolve_candidates<false, 256>(lc, n_cand, need, trow + n_above, dh, wtot, bc, dhw);
-  else resolve_candidates<true, 256>(crow, n_cand, need, trow + n_above, dh, wtot, bc);
+  int32_t* sout = srow ? srow + n_above : nullptr;
+  if (in_lds) resolve_candidates<false, 256>(lc, n_cand, need, trow + n_above, dh, wtot, bc, dhw, sout, pm, row / Hkv);
+  else resolve_candidates<true, 256>(crow, n_cand, need, trow + n_above, dh, wtot, bc, nullptr, sout, pm, row / Hkv);
 #ifdef FASA_TRACE
   tt[5] = wall_clock64();
   if (t == 0 && row == 0) printf("select last(row0,slice %d): thr %llu pos %llu ticket %llu candload %llu resolve %llu ncand %d need %d (x10ns)\n", slice, tt[1]-tt[0], tt[2]-tt[1], tt[3]-tt[2], tt[4]-tt[3], tt[5]-tt[4], n_cand, need);
@@ -292,10 +303,14 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
 }
 
 // budget >= N: every token is selected
-__global__ __launch_bounds__(256) void select_all_kernel(int32_t* __restrict__ T, int N) {
+__global__ __launch_bounds__(256) void select_all_kernel(int32_t* __restrict__ T, int N, int Hkv,
+                                                         PageMap pm, int32_t* __restrict__ Tslot) {
   const int row = blockIdx.y;
   const int n = blockIdx.x * 256 + threadIdx.x;
-  if (n < N) T[(size_t)row * N + n] = n;
+  if (n < N) {
+    T[(size_t)row * N + n] = n;
+    if (Tslot) Tslot[(size_t)row * N + n] = kv_slot(pm, row / Hkv, n);
+  }
 }
 
 // zeroes the histogram and the row counters: 1-D grid, one uint4 per thread
@@ -305,18 +320,19 @@ __global__ __launch_bounds__(256) void ws_clear_kernel(uint4* __restrict__ p, si
 }
 
 hipError_t launch_select(const fasa_shape& s, const float* S, const uint32_t* hist, RowCtl* ctl,
-                         uint2* cand, int32_t* T, hipStream_t st, RaggedLens rl) {
+                         uint2* cand, int32_t* T, hipStream_t st, RaggedLens rl, PageMap pm,
+                         int32_t* Tslot) {
   const int rows = s.batch * s.n_kv_heads;
   const bool ragged = rl.n_ctx != nullptr || rl.budget != nullptr;
   if (s.budget >= s.n_ctx && !ragged) {
     dim3 grid((s.n_ctx + 255) / 256, rows), block(256);
-    return launch("fasa_select_all", select_all_kernel, grid, block, st, T, s.n_ctx);
+    return launch("fasa_select_all", select_all_kernel, grid, block, st, T, s.n_ctx, s.n_kv_heads, pm, Tslot);
   }
   const int nslices = (s.n_ctx + kSelTokPerBlock - 1) / kSelTokPerBlock;
   const int t_pitch = s.budget < s.n_ctx ? s.budget : s.n_ctx;
   return launch("fasa_select", select_kernel, dim3(rows * nslices), dim3(256), st, S,
                 const_cast<uint32_t*>(hist), ctl, cand, T, rows, nslices, s.n_ctx, s.n_cap, s.budget,
-                t_pitch, s.n_kv_heads, rl.n_ctx, rl.budget);
+                t_pitch, s.n_kv_heads, rl.n_ctx, rl.budget, pm, Tslot);
 }
 
 hipError_t launch_ws_clear(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, hipStream_t st) {

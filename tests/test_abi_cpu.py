@@ -25,7 +25,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = _declared()
-    assert len(names) >= 23 and "fasa_decode_step" in names and "fasa_pack_kcache" in names
+    assert len(names) >= 25 and "fasa_decode_step" in names and "fasa_pack_kcache" in names
     lib = C.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -121,6 +121,28 @@ def test_null_and_misaligned_pointers():
     assert L.fasa_decode_step_ragged(C.byref(s), A, A, A, A, A, None, None, A + 2, None, A, A, A, A, 1 << 40, None) == fb.FASA_EINVAL
     assert L.fasa_decode_step_ragged(C.byref(s), A, A, A, A, A, None, None, A, A + 1, A, A, A, A, 1 << 40, None) == fb.FASA_EINVAL
     assert L.fasa_decode_step_ragged(C.byref(s), A, A, A, A, A, None, None, A, None, A, A, A, A, 0, None) == fb.FASA_EWORKSPACE
+
+
+def test_paging_is_validated():
+    s = _shape()
+    L = fb.lib
+    ok = fb.FasaPaging(A, 64, 16, 100, 0)
+    call = lambda pg: L.fasa_decode_step_paged(C.byref(s), C.byref(pg), A, A, A, A, A, None, None, None, None,
+                                               A, A, A, A, 0, None)
+    assert call(ok) == fb.FASA_EWORKSPACE                                 # everything else is fine
+    assert call(fb.FasaPaging(None, 64, 16, 100, 0)) == fb.FASA_EINVAL    # no table
+    assert call(fb.FasaPaging(A + 2, 64, 16, 100, 0)) == fb.FASA_EINVAL   # misaligned table
+    assert call(fb.FasaPaging(A, 64, 24, 100, 0)) == fb.FASA_EINVAL       # page size not a power of two
+    assert call(fb.FasaPaging(A, 64, 0, 100, 0)) == fb.FASA_EINVAL
+    assert call(fb.FasaPaging(A, 4, 16, 100, 0)) == fb.FASA_EINVAL        # table does not cover n_ctx
+    assert call(fb.FasaPaging(A, 64, 16, 0, 0)) == fb.FASA_EINVAL         # empty pool
+    assert call(fb.FasaPaging(A, 64, 16, 100, 1)) == fb.FASA_EINVAL       # reserved
+    assert call(fb.FasaPaging(A, 64, 1024, 1 << 22, 0)) == fb.FASA_EUNSUPPORTED   # slots beyond 2^31
+    assert L.fasa_decode_step_paged(C.byref(s), None, A, A, A, A, A, None, None, None, None, A, A, A, A, 1 << 40,
+                                    None) == fb.FASA_EINVAL
+    small = fb.FasaPaging(A, 4, 16, 100, 0)
+    assert L.fasa_pack_kcache_paged(C.byref(s), C.byref(small), A, A, A, 0, 65, None) == fb.FASA_EINVAL  # table ends at 64
+    assert L.fasa_pack_kcache_paged(C.byref(s), C.byref(ok), A, A, A, 5, 5, None) == fb.FASA_OK         # empty range
 
 
 def test_workspace_too_small():
