@@ -268,9 +268,14 @@ int fasa_dense_attend(const fasa_shape* shape, const void* q, const void* K, con
   return attend_common(shape, true, q, K, V, nullptr, O, ws, ws_bytes, stream);
 }
 
-int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,
-                     const int32_t* fc_idx, const void* k_new, const void* v_new, float* S,
-                     int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream) {
+// The three forms of the fused step share one body.  paging == nullptr: contiguous cache.
+// by_sequence: lengths (and optionally budgets) come from device arrays; the launch sequence must
+// then not depend on them, so the histogram path is always taken (it also covers a sequence whose
+// budget reaches its length).
+static int decode_step_common(const fasa_shape* shape, const fasa_paging* paging, const void* q, void* K,
+                              void* V, void* Kp, const int32_t* fc_idx, const void* k_new,
+                              const void* v_new, const int32_t* n_ctx_seq, const int32_t* budget_seq,
+                              float* S, int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_shape(shape, kNeedCtx | kNeedBudget | kNeedFc | kNeedStrides);
   if (rc != FASA_OK) return rc;
   if (!q || !K || !V || !Kp || !fc_idx || !S || !T || !O) return FASA_EINVAL;
@@ -278,52 +283,47 @@ int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, v
   if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(Kp) || !aligned16(fc_idx) ||
       !aligned16(S) || !aligned16(T) || !aligned16(O) || !aligned16(k_new) || !aligned16(v_new))
     return FASA_EINVAL;
-  rc = check_ws(shape, ws, ws_bytes);
+  if (((uintptr_t)n_ctx_seq & 3u) || ((uintptr_t)budget_seq & 3u)) return FASA_EINVAL;
+  PageMap pm = kNoPaging;
+  if (paging) {
+    rc = check_paging(paging, shape, &pm);
+    if (rc != FASA_OK) return rc;
+  }
+  rc = check_ws(shape, ws, ws_bytes, paging != nullptr);
   if (rc != FASA_OK) return rc;
   const WsLayout w = ws_layout(*shape);
   char* base = (char*)ws;
   uint32_t* hist = (uint32_t*)(base + w.hist_off);
   RowCtl* ctl = (RowCtl*)(base + w.ctl_off);
   uint2* cand = (uint2*)(base + w.cand_off);
+  int32_t* Tslot = paging ? (int32_t*)(base + w.tslot_off) : nullptr;
   hipStream_t st = (hipStream_t)stream;
-  const bool select_all = shape->budget >= shape->n_ctx;
-  if (k_new) FASA_HIP(launch_append(*shape, K, V, Kp, fc_idx, k_new, v_new, st));
-  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, select_all ? nullptr : hist, st));
-  FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st));
-  FASA_HIP(launch_attend(*shape, false, q, K, V, T, O, ctl, (float*)(base + w.part_acc_off),
-                         (float*)(base + w.part_ml_off), st));
+  const RaggedLens rl{n_ctx_seq, budget_seq};
+  const bool by_sequence = n_ctx_seq != nullptr || budget_seq != nullptr;
+  const bool select_all = !by_sequence && shape->budget >= shape->n_ctx;
+  if (k_new) FASA_HIP(launch_append(*shape, K, V, Kp, fc_idx, k_new, v_new, st, rl, pm));
+  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, select_all ? nullptr : hist, st, rl));
+  FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st, rl, pm, Tslot));
+  // paged cache: the attention kernel gathers by pool slot and does not read the table again
+  FASA_HIP(launch_attend(*shape, false, q, K, V, paging ? Tslot : T, O, ctl, (float*)(base + w.part_acc_off),
+                         (float*)(base + w.part_ml_off), st, rl, pm));
   return FASA_OK;
+}
+
+int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,
+                     const int32_t* fc_idx, const void* k_new, const void* v_new, float* S,
+                     int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream) {
+  return decode_step_common(shape, nullptr, q, K, V, Kp, fc_idx, k_new, v_new, nullptr, nullptr, S, T, O, ws,
+                            ws_bytes, stream);
 }
 
 int fasa_decode_step_ragged(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,
                             const int32_t* fc_idx, const void* k_new, const void* v_new,
                             const int32_t* n_ctx_seq, const int32_t* budget_seq, float* S, int32_t* T,
                             float* O, void* ws, size_t ws_bytes, void* stream) {
-  int rc = check_shape(shape, kNeedCtx | kNeedBudget | kNeedFc | kNeedStrides);
-  if (rc != FASA_OK) return rc;
-  if (!q || !K || !V || !Kp || !fc_idx || !S || !T || !O || !n_ctx_seq) return FASA_EINVAL;
-  if ((k_new == nullptr) != (v_new == nullptr)) return FASA_EINVAL;
-  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(Kp) || !aligned16(fc_idx) ||
-      !aligned16(S) || !aligned16(T) || !aligned16(O) || !aligned16(k_new) || !aligned16(v_new))
-    return FASA_EINVAL;
-  if (((uintptr_t)n_ctx_seq & 3u) || ((uintptr_t)budget_seq & 3u)) return FASA_EINVAL;
-  rc = check_ws(shape, ws, ws_bytes);
-  if (rc != FASA_OK) return rc;
-  const WsLayout w = ws_layout(*shape);
-  char* base = (char*)ws;
-  uint32_t* hist = (uint32_t*)(base + w.hist_off);
-  RowCtl* ctl = (RowCtl*)(base + w.ctl_off);
-  uint2* cand = (uint2*)(base + w.cand_off);
-  hipStream_t st = (hipStream_t)stream;
-  const RaggedLens rl{n_ctx_seq, budget_seq};
-  // the launch sequence never depends on the lengths (they are not known on the host): always the
-  // histogram path, which also covers a sequence whose budget reaches its length
-  if (k_new) FASA_HIP(launch_append(*shape, K, V, Kp, fc_idx, k_new, v_new, st, rl));
-  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, hist, st, rl));
-  FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st, rl));
-  FASA_HIP(launch_attend(*shape, false, q, K, V, T, O, ctl, (float*)(base + w.part_acc_off),
-                         (float*)(base + w.part_ml_off), st, rl));
-  return FASA_OK;
+  if (!n_ctx_seq) return FASA_EINVAL;
+  return decode_step_common(shape, nullptr, q, K, V, Kp, fc_idx, k_new, v_new, n_ctx_seq, budget_seq, S, T, O,
+                            ws, ws_bytes, stream);
 }
 
 int fasa_pack_kcache_paged(const fasa_shape* shape, const fasa_paging* paging, const void* K,
@@ -346,36 +346,9 @@ int fasa_decode_step_paged(const fasa_shape* shape, const fasa_paging* paging, c
                            void* V, void* Kp, const int32_t* fc_idx, const void* k_new, const void* v_new,
                            const int32_t* n_ctx_seq, const int32_t* budget_seq, float* S, int32_t* T,
                            float* O, void* ws, size_t ws_bytes, void* stream) {
-  int rc = check_shape(shape, kNeedCtx | kNeedBudget | kNeedFc | kNeedStrides);
-  if (rc != FASA_OK) return rc;
-  if (!q || !K || !V || !Kp || !fc_idx || !S || !T || !O) return FASA_EINVAL;
-  if ((k_new == nullptr) != (v_new == nullptr)) return FASA_EINVAL;
-  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(Kp) || !aligned16(fc_idx) ||
-      !aligned16(S) || !aligned16(T) || !aligned16(O) || !aligned16(k_new) || !aligned16(v_new))
-    return FASA_EINVAL;
-  if (((uintptr_t)n_ctx_seq & 3u) || ((uintptr_t)budget_seq & 3u)) return FASA_EINVAL;
-  PageMap pm;
-  rc = check_paging(paging, shape, &pm);
-  if (rc != FASA_OK) return rc;
-  rc = check_ws(shape, ws, ws_bytes);
-  if (rc != FASA_OK) return rc;
-  const WsLayout w = ws_layout(*shape);
-  char* base = (char*)ws;
-  uint32_t* hist = (uint32_t*)(base + w.hist_off);
-  RowCtl* ctl = (RowCtl*)(base + w.ctl_off);
-  uint2* cand = (uint2*)(base + w.cand_off);
-  int32_t* Tslot = (int32_t*)(base + w.tslot_off);
-  hipStream_t st = (hipStream_t)stream;
-  const RaggedLens rl{n_ctx_seq, budget_seq};
-  const bool ragged = n_ctx_seq != nullptr || budget_seq != nullptr;
-  const bool select_all = !ragged && shape->budget >= shape->n_ctx;
-  if (k_new) FASA_HIP(launch_append(*shape, K, V, Kp, fc_idx, k_new, v_new, st, rl, pm));
-  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, select_all ? nullptr : hist, st, rl));
-  FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st, rl, pm, Tslot));
-  // the attention kernel gathers by pool slot: the block table is not read again
-  FASA_HIP(launch_attend(*shape, false, q, K, V, Tslot, O, ctl, (float*)(base + w.part_acc_off),
-                         (float*)(base + w.part_ml_off), st, rl, pm));
-  return FASA_OK;
+  if (!paging) return FASA_EINVAL;
+  return decode_step_common(shape, paging, q, K, V, Kp, fc_idx, k_new, v_new, n_ctx_seq, budget_seq, S, T, O,
+                            ws, ws_bytes, stream);
 }
 
 size_t fasa_offload_stage_bytes(const fasa_shape* shape) {
