@@ -30,7 +30,7 @@ __device__ __forceinline__ void fma_pairs<float>(const uint4& w, float qlo, floa
 constexpr int kScoreFB = 16;  // FC planes in flight per thread
 
 // 1-D grid of rows * nslices workgroups, nslices = ceil(N / (256 * TPT)).  One 16-byte load per
-// thread per FC plane: a wave reads 1 KiB contiguous from each plane.  NB > 0: F == 16 * NB and all
+// thread per FC plane: a wave reads 1 KiB contiguous from each plane.  NB > 0: F == 8 * NB and all
 // F plane loads of a thread are in flight at once, issued as straight-line code; NB == 0: any F,
 // 16 planes at a time.
 //
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
                                                     int n_cap, const int32_t* __restrict__ n_ctx_seq) {
   constexpr int D = kHeadDim;
   constexpr int TPT = ScoreTraits<ET>::TPT;
-  constexpr int NW = NB ? NB * kScoreFB : kScoreFB;
+  constexpr int NW = NB ? NB * 8 : kScoreFB;
   __shared__ float qsum[256];      // [t]: sum over the group of q[., t mod 128] (upper half: copies)
   __shared__ int32_t fcl[256];     // [t]: fc_idx[h][min(t, F - 1)]
   __shared__ float2 qs[D / 2];
@@ -206,9 +206,11 @@ template <typename ET, bool HIST>
 static hipError_t launch_score_h(const fasa_shape& s, const void* q, const void* Kp,
                                  const int32_t* fc_idx, float* S, uint32_t* hist, hipStream_t st,
                                  RaggedLens rl) {
-  switch (s.n_fc) {
-    case kScoreFB: return launch_score_v<ET, HIST, 1>(s, q, Kp, fc_idx, S, hist, st, rl);
-    case 2 * kScoreFB: return launch_score_v<ET, HIST, 2>(s, q, Kp, fc_idx, S, hist, st, rl);
+  switch (s.n_fc) {   // the usual settings (an eighth to a half of the FCs) get straight-line loads
+    case 8: return launch_score_v<ET, HIST, 1>(s, q, Kp, fc_idx, S, hist, st, rl);
+    case 16: return launch_score_v<ET, HIST, 2>(s, q, Kp, fc_idx, S, hist, st, rl);
+    case 24: return launch_score_v<ET, HIST, 3>(s, q, Kp, fc_idx, S, hist, st, rl);
+    case 32: return launch_score_v<ET, HIST, 4>(s, q, Kp, fc_idx, S, hist, st, rl);
     default: return launch_score_v<ET, HIST, 0>(s, q, Kp, fc_idx, S, hist, st, rl);
   }
 }

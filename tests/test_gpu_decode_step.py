@@ -89,6 +89,13 @@ REDUCED = {
     "budget_gt_n": dict(cid=1, n_ctx=130, budget=4096, n_kv_heads=2, n_q_heads=8),
     "n_1": dict(cid=1, n_ctx=1, budget=1, n_kv_heads=2, n_q_heads=4),
     "f32_g1_ragged": dict(cid=0, n_ctx=2049, budget=65),
+    # every specialisation of the scoring kernel (F = 8, 16, 24, 32) and the generic one, both storage types
+    "fc8": dict(cid=1, n_ctx=3000, budget=200, n_fc=8),
+    "fc24": dict(cid=1, n_ctx=3007, budget=200, n_fc=24),
+    "fc24_f32": dict(cid=0, n_ctx=2500, budget=100, n_fc=24),
+    "fc8_f32": dict(cid=0, n_ctx=1030, budget=100, n_fc=8),
+    "fc40": dict(cid=1, n_ctx=3000, budget=200, n_fc=40),
+    "fc64": dict(cid=1, n_ctx=2100, budget=200, n_fc=64),
 }
 
 
