@@ -187,10 +187,12 @@ __global__ __launch_bounds__(256) void hist_kernel(const float* __restrict__ S,
   }
   __syncthreads();
   uint32_t* gh = hist + (size_t)row * kHistBins;
-  for (int i = t; i < kHistBins; i += 256) {
-    const uint32_t c = lh[i];
-    if (c) atomicAdd(&gh[i], c);
-  }
+  uint32_t c[kHistBins / 256];
+#pragma unroll
+  for (int k = 0; k < kHistBins / 256; ++k) c[k] = lh[t + 256 * k];
+#pragma unroll
+  for (int k = 0; k < kHistBins / 256; ++k)
+    if (c[k]) atomicAdd(&gh[t + 256 * k], c[k]);
 }
 
 template <typename ET, bool HIST, int NB>

@@ -71,6 +71,16 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
   const uint32_t out_cap = (uint32_t)need;  // never write past the row's share of T
   unsigned long long prefix = 0;
   int shift = 52;            // the composite has 52 significant bits: digits at 44, 36, ..., 4, 0
+  // The list is walked four entries per thread at a time, the four reads issued together (one LDS
+  // or memory round trip per chunk instead of one per entry); entry u of chunk i0 is i0 + u*NT + t.
+  constexpr int CH = 4;
+  auto load_chunk = [&](int i0, uint2 (&c)[CH]) {
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+      const int i = min(i0 + u * NT + t, n - 1);
+      c[u] = SHARED_SRC ? ld_agent(&cand[i]) : cand[i];
+    }
+  };
 #ifdef FASA_TRACE
   unsigned long long rt[5]; for (int i = 0; i < 5; ++i) rt[i] = wall_clock64();
   int npass = 0;
@@ -82,9 +92,12 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
       for (int i = t; i < kHistBins; i += NT) dhw[i] = 0;
       if (t == 0) { bc[0] = 0; bc[1] = 0; bc[2] = 0; }
       __syncthreads();
-      for (int i = t; i < n; i += NT) {
-        const unsigned long long c = cand_composite(SHARED_SRC ? ld_agent(&cand[i]) : cand[i]);
-        atomicAdd(&dhw[(uint32_t)(c >> 40)], 1u);
+      for (int i0 = 0; i0 < n; i0 += CH * NT) {
+        uint2 c[CH];
+        load_chunk(i0, c);
+#pragma unroll
+        for (int u = 0; u < CH; ++u)
+          if (i0 + u * NT + t < n) atomicAdd(&dhw[(uint32_t)(cand_composite(c[u]) >> 40)], 1u);
       }
       __syncthreads();
 #ifdef FASA_TRACE
@@ -115,9 +128,15 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
 #endif
       if (t < 256) dh[t] = 0;
       __syncthreads();
-      for (int i = t; i < n; i += NT) {
-        const unsigned long long c = cand_composite(SHARED_SRC ? ld_agent(&cand[i]) : cand[i]);
-        if ((c >> (shift + width)) == prefix) atomicAdd(&dh[(uint32_t)(c >> shift) & ((1u << width) - 1u)], 1u);
+      for (int i0 = 0; i0 < n; i0 += CH * NT) {
+        uint2 c[CH];
+        load_chunk(i0, c);
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+          const unsigned long long cc = cand_composite(c[u]);
+          if (i0 + u * NT + t < n && (cc >> (shift + width)) == prefix)
+            atomicAdd(&dh[(uint32_t)(cc >> shift) & ((1u << width) - 1u)], 1u);
+        }
       }
       __syncthreads();
       const uint32_t cnt = t < 256 ? dh[t] : 0u;
@@ -141,14 +160,29 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
 #ifdef FASA_TRACE
   rt[3] = wall_clock64();
 #endif
-  for (int i = t; i < n; i += NT) {
-    const uint2 c = SHARED_SRC ? ld_agent(&cand[i]) : cand[i];
-    if ((cand_composite(c) >> shift) >= prefix) {
-      const uint32_t pos = atomicAdd(&bc[3], 1u);
-      if (pos < out_cap) {
-        out[pos] = (int32_t)c.y;
-        if (out_slot) out_slot[pos] = kv_slot(pm, b, (int)c.y);   // paged cache: where the row lives
+  // output: one position atomic per wave and chunk (ballots give every taken entry its offset)
+  for (int i0 = 0; i0 < n; i0 += CH * NT) {
+    uint2 c[CH];
+    load_chunk(i0, c);
+    unsigned long long m[CH];
+    uint32_t taken = 0;
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+      m[u] = __ballot(i0 + u * NT + t < n && (cand_composite(c[u]) >> shift) >= prefix);
+      taken += (uint32_t)__popcll(m[u]);
+    }
+    uint32_t pos = 0;
+    if (lane_id() == 0 && taken) pos = atomicAdd(&bc[3], taken);
+    pos = (uint32_t)__builtin_amdgcn_readfirstlane((int)pos);
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+      const uint32_t mine = pos + __builtin_amdgcn_mbcnt_hi((uint32_t)(m[u] >> 32),
+                                                            __builtin_amdgcn_mbcnt_lo((uint32_t)m[u], 0u));
+      if (((m[u] >> lane_id()) & 1ull) && mine < out_cap) {
+        out[mine] = (int32_t)c[u].y;
+        if (out_slot) out_slot[mine] = kv_slot(pm, b, (int)c[u].y);   // paged cache: where the row lives
       }
+      pos += (uint32_t)__popcll(m[u]);
     }
   }
 #ifdef FASA_TRACE
@@ -277,7 +311,15 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   if (t == 0) bc[3] = 0;
   const bool in_lds = n_cand <= kCandLds;
   if (in_lds) {
-    for (int i = t; i < n_cand; i += 256) lc[i] = ld_agent(&crow[i]);
+    // four loads per thread in flight: up to 1024 candidates cost one memory round trip
+    for (int i0 = 0; i0 < n_cand; i0 += 4 * 256) {
+      uint2 c[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) c[u] = ld_agent(&crow[min(i0 + u * 256 + t, n_cand - 1)]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (i0 + u * 256 + t < n_cand) lc[i0 + u * 256 + t] = c[u];
+    }
   }
   __syncthreads();
 #ifdef FASA_TRACE
