@@ -171,6 +171,11 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
       m[u] = __ballot(i0 + u * NT + t < n && (cand_composite(c[u]) >> shift) >= prefix);
       taken += (uint32_t)__popcll(m[u]);
     }
+    int sl[CH];
+    if (out_slot) {   // paged cache: where the rows live; looked up before the stores below
+#pragma unroll
+      for (int u = 0; u < CH; ++u) sl[u] = kv_slot(pm, b, (int)(c[u].y & 0x7fffffffu));
+    }
     uint32_t pos = 0;
     if (lane_id() == 0 && taken) pos = atomicAdd(&bc[3], taken);
     pos = (uint32_t)__builtin_amdgcn_readfirstlane((int)pos);
@@ -180,7 +185,7 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
                                                             __builtin_amdgcn_mbcnt_lo((uint32_t)m[u], 0u));
       if (((m[u] >> lane_id()) & 1ull) && mine < out_cap) {
         out[mine] = (int32_t)c[u].y;
-        if (out_slot) out_slot[mine] = kv_slot(pm, b, (int)c[u].y);   // paged cache: where the row lives
+        if (out_slot) out_slot[mine] = sl[u];
       }
       pos += (uint32_t)__popcll(m[u]);
     }
@@ -263,6 +268,15 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
     win |= (ok && bin > tbin) ? (1u << k) : 0u;
     cnd |= (ok && bin == tbin) ? (1u << k) : 0u;
   }
+  // paged cache: the pool slots of this thread's tokens are looked up now, all loads together and
+  // before any store (a load issued after stores would wait for every one of them to be acknowledged)
+  int32_t* srow = Tslot ? Tslot + (size_t)row * t_pitch : nullptr;
+  int slot[kSelPerThread];
+  if (srow) {
+#pragma unroll
+    for (int k = 0; k < kSelPerThread; ++k)
+      slot[k] = kv_slot(pm, row / Hkv, min(base + ((k >> 2) * 256 + t) * 4 + (k & 3), N - 1));
+  }
   uint32_t pw, pc, tw, tc;
   block256_prefix2(__popc(win), __popc(cnd), wtot, pw, pc, tw, tc);
   if (t == 0) {
@@ -278,7 +292,6 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
 #endif
   uint32_t bw = bc[0] + pw, bcand = bc[1] + pc;
   int32_t* trow = T + (size_t)row * t_pitch;
-  int32_t* srow = Tslot ? Tslot + (size_t)row * t_pitch : nullptr;
   uint2* crow = cand + (size_t)row * n_cap;
 #pragma unroll
   for (int k = 0; k < kSelPerThread; ++k) {
@@ -287,7 +300,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
     // histogram that does not match S can never turn into an out-of-range store
     if ((win & (1u << k)) && bw < (uint32_t)bsel) {
       trow[bw] = n;
-      if (srow) srow[bw] = kv_slot(pm, row / Hkv, n);
+      if (srow) srow[bw] = slot[k];
       ++bw;
     }
     // candidates are read by the row's last workgroup: published with agent-scope stores
