@@ -17,8 +17,11 @@
 
 namespace fasa {
 
-constexpr int kSelTokPerBlock = 2048;           // slice of a row filtered by one workgroup
-constexpr int kSelPerThread = kSelTokPerBlock / 256;
+// Slice of a row filtered by one workgroup: 2048 tokens, or 1024 when that still leaves at most two
+// workgroups per CU (small problems are latency-bound: the shorter slice shortens every workgroup;
+// large ones are throughput-bound: fewer, longer workgroups publish and queue less).
+constexpr int kSelTokLong = 2048, kSelTokShort = 1024;
+constexpr int kSelShortMaxBlocks = 512;
 constexpr int kCandLds = 4096;                  // candidates resolved out of LDS; more: global reads
 
 __device__ __forceinline__ unsigned long long cand_composite(uint2 c) {
@@ -196,7 +199,8 @@ __device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* 
 #endif
 }
 
-// 1-D grid of rows * nslices workgroups, nslices = ceil(N / kSelTokPerBlock)
+// 1-D grid of rows * nslices workgroups, nslices = ceil(N / TPB), TPB tokens per workgroup
+template <int TPB>
 __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S,
                                                      uint32_t* __restrict__ hist,
                                                      RowCtl* __restrict__ ctl,
@@ -206,6 +210,8 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
                                                      int Hkv, const int32_t* __restrict__ n_ctx_seq,
                                                      const int32_t* __restrict__ budget_seq, PageMap pm,
                                                      int32_t* __restrict__ Tslot) {
+  constexpr int kSelTokPerBlock = TPB;
+  constexpr int kSelPerThread = TPB / 256;
   __shared__ uint32_t wtot[8];
   __shared__ uint32_t bc[4];
   __shared__ uint32_t thr[3];  // threshold bin, tokens above it, tokens inside it
@@ -383,9 +389,14 @@ hipError_t launch_select(const fasa_shape& s, const float* S, const uint32_t* hi
     dim3 grid((s.n_ctx + 255) / 256, rows), block(256);
     return launch("fasa_select_all", select_all_kernel, grid, block, st, T, s.n_ctx, s.n_kv_heads, pm, Tslot);
   }
-  const int nslices = (s.n_ctx + kSelTokPerBlock - 1) / kSelTokPerBlock;
   const int t_pitch = s.budget < s.n_ctx ? s.budget : s.n_ctx;
-  return launch("fasa_select", select_kernel, dim3(rows * nslices), dim3(256), st, S,
+  const int n_short = (s.n_ctx + kSelTokShort - 1) / kSelTokShort;
+  if ((long long)rows * n_short <= kSelShortMaxBlocks)
+    return launch("fasa_select", select_kernel<kSelTokShort>, dim3(rows * n_short), dim3(256), st, S,
+                  const_cast<uint32_t*>(hist), ctl, cand, T, rows, n_short, s.n_ctx, s.n_cap, s.budget,
+                  t_pitch, s.n_kv_heads, rl.n_ctx, rl.budget, pm, Tslot);
+  const int nslices = (s.n_ctx + kSelTokLong - 1) / kSelTokLong;
+  return launch("fasa_select", select_kernel<kSelTokLong>, dim3(rows * nslices), dim3(256), st, S,
                 const_cast<uint32_t*>(hist), ctl, cand, T, rows, nslices, s.n_ctx, s.n_cap, s.budget,
                 t_pitch, s.n_kv_heads, rl.n_ctx, rl.budget, pm, Tslot);
 }
