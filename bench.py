@@ -590,6 +590,9 @@ def main():
         "hbm": {"alg_bytes": model["alg"], "alg_plus_intermediate_bytes": model["alg_plus_intermediates"],
                 "step_gbps": round(model["alg"] / us_per_step / 1e3, 1),
                 "step_frac_of_peak": round(model["alg"] / us_per_step / 1e3 / HBM_PEAK_GBPS, 4),
+                # the same with the intermediates (S written and re-read, T) counted: the bytes actually touched
+                "step_touched_gbps": round(model["alg_plus_intermediates"] / us_per_step / 1e3, 1),
+                "step_touched_frac_of_peak": round(model["alg_plus_intermediates"] / us_per_step / 1e3 / HBM_PEAK_GBPS, 4),
                 "kernel_time_gbps": round(model["alg"] / sum_kernel_us / 1e3, 1),
                 "kernel_time_frac_of_peak": round(model["alg"] / sum_kernel_us / 1e3 / HBM_PEAK_GBPS, 4),
                 # second denominator: what a plain 256 MiB device copy moves (read + write) on this machine
