@@ -7,11 +7,13 @@
 //            from it upwards at least B;
 //   filter   several workgroups per row stream S once; tokens above the threshold bin are winners
 //            and go straight to T, tokens inside it are appended to a candidate list; positions
-//            come from a block-wide prefix sum plus ONE atomic per workgroup and counter;
+//            come from a block-wide prefix sum plus ONE 64-bit atomic per workgroup that reserves
+//            both ranges;
 //   final    the last workgroup of the row to finish resolves the candidates exactly: radix
-//            select, 8 bits a pass, over the 52-bit composite (low 20 key bits : ~index), which
-//            is unique per token, so exactly B - |winners| candidates come out.  It then zeroes
-//            the row's histogram and counters, which leaves the workspace clean for the next call.
+//            select (first digit 12 bits, then 8 bits a pass) over the 52-bit composite
+//            (low 20 key bits : ~index), which is unique per token, so exactly B - |winners|
+//            candidates come out.  It then zeroes the row's histogram and counters, which leaves
+//            the workspace clean for the next call.
 #include "fasa_device.h"
 #include "fasa_internal.h"
 
