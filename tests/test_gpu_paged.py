@@ -170,3 +170,42 @@ def test_stray_table_entries_are_clamped(fb):
     torch.cuda.synchronize()
     T = d.T.cpu().numpy()
     assert T.min() >= 0 and T.max() < w.n_ctx
+
+
+def _random_paged_cases(n_cases, seed=20260203):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n_cases):
+        G, hkv, batch = int(rng.integers(1, 9)), int(rng.choice([1, 2, 4, 8])), int(rng.integers(1, 5))
+        n_max = int(rng.integers(130, 5000))
+        budget = int(rng.integers(1, n_max + 1))
+        out.append(dict(G=G, hkv=hkv, batch=batch, page=int(rng.choice([1, 8, 16, 64, 128])),
+                        layout=str(rng.choice(["token_major", "head_major"])), n_max=n_max,
+                        n_fc=int(rng.choice([8, 16, 24, 32, int(rng.integers(1, 65))])),
+                        dtype="bf16" if rng.random() < 0.7 else "f32", budget=budget,
+                        lens=[int(rng.integers(1, n_max + 1)) for _ in range(batch)],
+                        buds=[int(rng.integers(1, budget + 1)) for _ in range(batch)]))
+    return out
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_ragged_paged_steps_with_append(fb, case):
+    """Seeded sweep over group size, head count, page size, block layout, F, storage type, lengths and
+    budgets: a ragged step with an append on a paged cache, every sequence against the oracle."""
+    from tests.gpu_util import to_dev
+    c = _random_paged_cases(12)[case]
+    print("random paged", case, c, flush=True)
+    w = W.WORKLOADS[1].scaled(batch=c["batch"], n_kv_heads=c["hkv"], n_q_heads=c["hkv"] * c["G"], n_fc=c["n_fc"],
+                              n_ctx=c["n_max"], budget=c["budget"], dtype=c["dtype"])
+    x = W.make_inputs(w, n_cap=(c["n_max"] + 127) // 128 * 128)
+    d = PagedDevice(fb, w, x, c["page"], c["layout"], seed=case)
+    fb.fasa_pack_kcache_paged(d.shape, d.paging, d.K, d.fc_idx, d.Kp, 0, c["n_max"])
+    a = W.make_append(w, x["fc_idx"], step=1, n_before=c["lens"][0])
+    K, V = x["K"].copy(), x["V"].copy()
+    for b, n in enumerate(c["lens"]):
+        K[b, :, n - 1], V[b, :, n - 1] = a["k_new"][b], a["v_new"][b]
+    fb.fasa_decode_step_paged(d.shape, d.paging, to_dev(a["q"]), d.K, d.V, d.Kp, d.fc_idx, to_dev(a["k_new"]),
+                              to_dev(a["v_new"]), i32_dev(c["lens"]), i32_dev(c["buds"]), d.S, d.T, d.O, d.ws, d.ws_bytes)
+    torch.cuda.synchronize()
+    compare_ragged(w, a["q"], K, V, x["fc_idx"], d, c["lens"], [min(b_, n) for b_, n in zip(c["buds"], c["lens"])],
+                   min(c["budget"], c["n_max"]))
