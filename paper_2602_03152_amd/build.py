@@ -3,6 +3,10 @@
     python -m paper_2602_03152_amd.build
 
 Objects go to paper_2602_03152_amd/_build/, the library to paper_2602_03152_amd/libfasa.so.
+
+build(extra_flags=["-DFASA_TRACE"]) compiles in device-side stage timers: the selection and attention
+kernels then print, for row 0, how long each of their phases took (units of 10 ns, from the constant
+100 MHz counter).  For investigation only: the printing itself costs microseconds.
 """
 from __future__ import annotations
 
