@@ -301,8 +301,9 @@ static int decode_step_common(const fasa_shape* shape, const fasa_paging* paging
   const RaggedLens rl{n_ctx_seq, budget_seq};
   const bool by_sequence = n_ctx_seq != nullptr || budget_seq != nullptr;
   const bool select_all = !by_sequence && shape->budget >= shape->n_ctx;
-  if (k_new) FASA_HIP(launch_append(*shape, K, V, Kp, fc_idx, k_new, v_new, st, rl, pm));
-  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, select_all ? nullptr : hist, st, rl));
+  // the new row (if any) joins K, V and Kp inside the scoring kernel
+  const AppendArgs ap{k_new, v_new, K, V, pm};
+  FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, select_all ? nullptr : hist, st, rl, ap));
   FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st, rl, pm, Tslot));
   // paged cache: the attention kernel gathers by pool slot and does not read the table again
   FASA_HIP(launch_attend(*shape, false, q, K, V, paging ? Tslot : T, O, ctl, (float*)(base + w.part_acc_off),

@@ -116,15 +116,23 @@ inline hipError_t launch(const char* name, void (*kernel)(KArgs...), dim3 grid, 
 // ---------------------------------------------------------------------------------------------
 hipError_t launch_pack(const fasa_shape& s, const void* K, const int32_t* fc_idx, void* Kp,
                        int n_begin, int n_end, hipStream_t st, PageMap pm = kNoPaging);
+// A freshly decoded K/V row per (b, h) ([batch][n_kv_heads][head_dim]) that the scoring kernel
+// appends at token n_ctx - 1 (K, V: the caches, with the shape's strides; Kp gets the dominant pairs).
+// k_new == nullptr: nothing to append.
+struct AppendArgs {
+  const void* k_new;
+  const void* v_new;
+  void* K;
+  void* V;
+  PageMap pm;
+};
+constexpr AppendArgs kNoAppend = {nullptr, nullptr, nullptr, nullptr, {nullptr, 0, 0, 0}};
 // hist == nullptr: scores only
 hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
-                        float* S, uint32_t* hist, hipStream_t st, RaggedLens rl = {nullptr, nullptr});
+                        float* S, uint32_t* hist, hipStream_t st, RaggedLens rl = {nullptr, nullptr},
+                        AppendArgs ap = kNoAppend);
 // zeroes the histogram and the row counters (workspace initialisation)
 hipError_t launch_ws_clear(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, hipStream_t st);
-// appends the new K/V row (position n_ctx - 1) and its packed FCs
-hipError_t launch_append(const fasa_shape& s, void* K, void* V, void* Kp, const int32_t* fc_idx,
-                         const void* k_new, const void* v_new, hipStream_t st,
-                         RaggedLens rl = {nullptr, nullptr}, PageMap pm = kNoPaging);
 hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st);
 // Tslot (paged caches only, else null): receives the pool slot of every entry of T, same layout
 hipError_t launch_select(const fasa_shape& s, const float* S, const uint32_t* hist, RowCtl* ctl,

@@ -42,14 +42,24 @@ constexpr int kScoreFB = 16;  // FC planes in flight per thread
 //   2. the K planes (lanes beyond the row's length re-read its first tokens);
 //   3. wait for 1 only: group sum per head dim -> LDS, then lanes < F pick their FC's two
 //      components.  This and the LDS clearing run under the latency of 2.
-template <typename ET, bool HIST, int NB>
-__global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
-                                                    const ET* __restrict__ Kp,
+//
+// APPEND (paper Alg. 2, Split + UpdateCache before scoring): the step's freshly decoded K/V row of
+// every (b, h) joins the caches inside this kernel instead of a kernel of its own.  The row is token
+// N - 1.  Every lane fetches one element of (k_new | v_new) with the loads of 1; the new key goes
+// through LDS, lanes < F extract their FC's pair from it, the workgroup whose slice holds token
+// N - 1 writes the pairs to the Kp planes and the whole row to K and V, and the one thread that owns
+// the token replaces, in its registers, what it loaded from the (not yet written) planes.
+template <typename ET, bool HIST, int NB, bool APPEND>
+__global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET* Kp,
                                                     const int32_t* __restrict__ fc_idx,
                                                     float* __restrict__ S,
                                                     uint32_t* __restrict__ hist, int rows,
                                                     int nslices, int Hq, int Hkv, int F, int N_max,
-                                                    int n_cap, const int32_t* __restrict__ n_ctx_seq) {
+                                                    int n_cap, const int32_t* __restrict__ n_ctx_seq,
+                                                    const ET* __restrict__ k_new,
+                                                    const ET* __restrict__ v_new, ET* Kc, ET* Vc,
+                                                    long long sb, long long sh, long long sn,
+                                                    PageMap pm) {
   constexpr int D = kHeadDim;
   constexpr int TPT = ScoreTraits<ET>::TPT;
   constexpr int NW = NB ? NB * 8 : kScoreFB;
@@ -57,6 +67,8 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
   __shared__ int32_t fcl[256];     // [t]: fc_idx[h][min(t, F - 1)]
   __shared__ float2 qs[D / 2];
   __shared__ uint32_t lh[HIST ? kHistBins : 1];
+  __shared__ ET knew[APPEND ? D : 1];          // the new key row
+  __shared__ uint2 kpair[APPEND ? D / 2 : 1];  // per plane: the new key's (lo, hi) as stored in Kp
 
   int row, slice;
   row_slice_of_block(rows, nslices, row, slice);
@@ -72,6 +84,13 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
 #pragma unroll
   for (int g = 0; g < kMaxGroup; ++g) qcol[g] = qh[(size_t)min(g, G - 1) * D];   // beyond the group: its last head, not added
   const int32_t fci = fc_idx[h * F + min(t, F - 1)];
+  ET newkv = ET(0);
+  if constexpr (APPEND) newkv = (t < D ? k_new : v_new)[(size_t)row * D + (t & (D - 1))];
+  // the appended token: which workgroup and thread own it, and which of the thread's tokens it is
+  const int n_app = N - 1;
+  const bool own_wg = APPEND && n_app / (256 * TPT) == slice;
+  const bool own_thread = own_wg && (n_app - slice * 256 * TPT) / TPT == t;
+  const int kin = n_app % TPT;
 
   // ---- 2 ----
   const int n0 = (slice * 256 + t) * TPT;
@@ -95,7 +114,10 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
       sum += g < G ? a : 0.f;
     }
     qsum[t] = sum;
-    fcl[t] = fci;
+    fcl[t] = min(max(fci, 0), D / 2 - 1);   // LDS indices below stay in range whatever the list holds
+    if constexpr (APPEND) {
+      if (t < D) knew[t] = newkv;
+    }
   }
   if constexpr (HIST) {
     for (int i = t; i < kHistBins; i += 256) lh[i] = 0;
@@ -104,13 +126,44 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
   if (t < F) {
     const int i = fcl[t];
     qs[t] = make_float2(qsum[i], qsum[i + D / 2]);
+    if constexpr (APPEND) {
+      const ET lo = knew[i], hi = knew[i + D / 2];
+      if constexpr (sizeof(ET) == 2) kpair[t] = make_uint2((uint32_t)lo | ((uint32_t)hi << 16), 0u);
+      else kpair[t] = make_uint2(__float_as_uint(lo), __float_as_uint(hi));
+      if (own_wg) {
+        ET* o = Kp + (((size_t)row * F + t) * n_cap + n_app) * 2;
+        o[0] = lo;
+        o[1] = hi;
+      }
+    }
   }
   __syncthreads();
+  // the planes did not hold the appended token yet: its owner takes the pairs from LDS
+  auto patch = [&](uint4& wv, int pf) {
+    const uint2 kp2 = kpair[pf];
+    if constexpr (sizeof(ET) == 2) {
+      wv.x = kin == 0 ? kp2.x : wv.x;
+      wv.y = kin == 1 ? kp2.x : wv.y;
+      wv.z = kin == 2 ? kp2.x : wv.z;
+      wv.w = kin == 3 ? kp2.x : wv.w;
+    } else {
+      wv.x = kin == 0 ? kp2.x : wv.x;
+      wv.y = kin == 0 ? kp2.y : wv.y;
+      wv.z = kin == 1 ? kp2.x : wv.z;
+      wv.w = kin == 1 ? kp2.y : wv.w;
+    }
+  };
 
   float acc[TPT];
 #pragma unroll
   for (int k = 0; k < TPT; ++k) acc[k] = 0.f;
   if constexpr (NB > 0) {
+    if constexpr (APPEND) {
+      if (own_thread) {
+#pragma unroll
+        for (int u = 0; u < NW; ++u) patch(w[u], u);
+      }
+    }
 #pragma unroll
     for (int u = 0; u < NW; ++u) {
       const float2 qf = qs[u];
@@ -118,6 +171,13 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
     }
   } else {
     for (int f0 = 0;;) {
+      if constexpr (APPEND) {
+        if (own_thread) {
+#pragma unroll
+          for (int u = 0; u < kScoreFB; ++u)
+            if (u < nf) patch(w[u], f0 + u);
+        }
+      }
 #pragma unroll
       for (int u = 0; u < kScoreFB; ++u) {
         if (u < nf) {
@@ -147,6 +207,12 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q,
 #pragma unroll
       for (int k = 0; k < TPT; ++k)
         if (n0 + k < N) atomicAdd(&lh[score_key(acc[k]) >> kKeyLowBits], 1u);
+    }
+  }
+  if constexpr (APPEND) {
+    if (own_wg) {   // the whole new row to K (threads 0..127) and V (threads 128..255)
+      ET* dst = (t < D ? Kc : Vc) + kv_row_offset(pm, b, n_app, sb, sn) + h * sh + (t & (D - 1));
+      *dst = newkv;
     }
   }
   if constexpr (HIST) {
@@ -195,43 +261,50 @@ __global__ __launch_bounds__(256) void hist_kernel(const float* __restrict__ S,
     if (c[k]) atomicAdd(&gh[t + 256 * k], c[k]);
 }
 
-template <typename ET, bool HIST, int NB>
-static hipError_t launch_score_v(const fasa_shape& s, const void* q, const void* Kp,
-                                 const int32_t* fc_idx, float* S, uint32_t* hist, hipStream_t st,
-                                 RaggedLens rl) {
+template <typename ET, bool HIST, int NB, bool APPEND>
+static hipError_t launch_score_v(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
+                                 float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
+                                 const AppendArgs& ap) {
   const int rows = s.batch * s.n_kv_heads;
   const int per_block = 256 * ScoreTraits<ET>::TPT;
   const int nslices = (s.n_ctx + per_block - 1) / per_block;
-  return launch(HIST ? "fasa_score_hist" : "fasa_score", score_kernel<ET, HIST, NB>, dim3(rows * nslices),
-                dim3(256), st, (const ET*)q, (const ET*)Kp, fc_idx, S, hist, rows, nslices, s.n_q_heads,
-                s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap, rl.n_ctx);
+  return launch(HIST ? "fasa_score_hist" : "fasa_score", score_kernel<ET, HIST, NB, APPEND>,
+                dim3(rows * nslices), dim3(256), st, (const ET*)q, (ET*)Kp, fc_idx, S, hist, rows, nslices,
+                s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap, rl.n_ctx, (const ET*)ap.k_new,
+                (const ET*)ap.v_new, (ET*)ap.K, (ET*)ap.V, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
+                (long long)s.kv_stride_n, ap.pm);
 }
 
-template <typename ET, bool HIST>
-static hipError_t launch_score_h(const fasa_shape& s, const void* q, const void* Kp,
-                                 const int32_t* fc_idx, float* S, uint32_t* hist, hipStream_t st,
-                                 RaggedLens rl) {
+template <typename ET, bool HIST, bool APPEND>
+static hipError_t launch_score_h(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
+                                 float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
+                                 const AppendArgs& ap) {
   switch (s.n_fc) {   // the usual settings (an eighth to a half of the FCs) get straight-line loads
-    case 8: return launch_score_v<ET, HIST, 1>(s, q, Kp, fc_idx, S, hist, st, rl);
-    case 16: return launch_score_v<ET, HIST, 2>(s, q, Kp, fc_idx, S, hist, st, rl);
-    case 24: return launch_score_v<ET, HIST, 3>(s, q, Kp, fc_idx, S, hist, st, rl);
-    case 32: return launch_score_v<ET, HIST, 4>(s, q, Kp, fc_idx, S, hist, st, rl);
-    default: return launch_score_v<ET, HIST, 0>(s, q, Kp, fc_idx, S, hist, st, rl);
+    case 8: return launch_score_v<ET, HIST, 1, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    case 16: return launch_score_v<ET, HIST, 2, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    case 24: return launch_score_v<ET, HIST, 3, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    case 32: return launch_score_v<ET, HIST, 4, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    default: return launch_score_v<ET, HIST, 0, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
   }
 }
 
 template <typename ET>
-static hipError_t launch_score_t(const fasa_shape& s, const void* q, const void* Kp,
-                                 const int32_t* fc_idx, float* S, uint32_t* hist, hipStream_t st,
-                                 RaggedLens rl) {
-  return hist ? launch_score_h<ET, true>(s, q, Kp, fc_idx, S, hist, st, rl)
-              : launch_score_h<ET, false>(s, q, Kp, fc_idx, S, hist, st, rl);
+static hipError_t launch_score_t(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
+                                 float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
+                                 const AppendArgs& ap) {
+  if (ap.k_new)
+    return hist ? launch_score_h<ET, true, true>(s, q, Kp, fc_idx, S, hist, st, rl, ap)
+                : launch_score_h<ET, false, true>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+  return hist ? launch_score_h<ET, true, false>(s, q, Kp, fc_idx, S, hist, st, rl, ap)
+              : launch_score_h<ET, false, false>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
 }
 
 hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
-                        float* S, uint32_t* hist, hipStream_t st, RaggedLens rl) {
-  return s.dtype == FASA_BF16 ? launch_score_t<uint16_t>(s, q, Kp, fc_idx, S, hist, st, rl)
-                              : launch_score_t<float>(s, q, Kp, fc_idx, S, hist, st, rl);
+                        float* S, uint32_t* hist, hipStream_t st, RaggedLens rl, AppendArgs ap) {
+  // Kp is only written when a row is appended (ap.k_new != nullptr)
+  return s.dtype == FASA_BF16
+             ? launch_score_t<uint16_t>(s, q, const_cast<void*>(Kp), fc_idx, S, hist, st, rl, ap)
+             : launch_score_t<float>(s, q, const_cast<void*>(Kp), fc_idx, S, hist, st, rl, ap);
 }
 
 hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st) {
