@@ -39,10 +39,10 @@ LLC_BYTES = 256 << 20         # last-level (memory-side) cache the rotation has 
 # (workload config id, kernel name); bytes per launch.  None = not measured yet.
 MEASURED_TRAFFIC = {
     # profiles/decode_step_llama3_8b_layer_n32768_b2048_hbm_counters.txt
-    (1, "fasa_score_hist"): 16876376 + 1235328,
-    (1, "fasa_select"): 1393316 + 350147,
-    (1, "fasa_sparse_attend"): 9206448 + 1089792,
-    (1, "fasa_dense_attend"): 135503678 + 2162944,
+    (1, "fasa_score_hist"): 16876270 + 1235328,
+    (1, "fasa_select"): 1393282 + 350168,
+    (1, "fasa_sparse_attend"): 9206435 + 1089792,
+    (1, "fasa_dense_attend"): 135503614 + 2162944,
 }
 
 
