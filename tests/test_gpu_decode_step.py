@@ -251,6 +251,45 @@ def test_growing_cache_appends(fb):
         compare_step(w, a["q"], K, V, x["fc_idx"], d, n, b)
 
 
+APPEND_CASES = {
+    # every instance of the scoring kernel that appends: storage type x histogram or not x F variant,
+    # and the appended token first / last / alone in its thread's group of tokens
+    "bf16_f16": dict(cid=1, n_ctx=2049, budget=100),
+    "bf16_f16_last_of_four": dict(cid=1, n_ctx=2052, budget=100),
+    "bf16_generic_f": dict(cid=1, n_ctx=1500, budget=100, n_fc=21),
+    "bf16_generic_f_two_batches": dict(cid=1, n_ctx=1502, budget=100, n_fc=40),
+    "bf16_select_all": dict(cid=1, n_ctx=1027, budget=5000, n_kv_heads=2, n_q_heads=8),
+    "f32_f16": dict(cid=0, n_ctx=2050, budget=65),
+    "f32_f8_odd": dict(cid=0, n_ctx=1025, budget=65, n_fc=8),
+    "f32_select_all": dict(cid=0, n_ctx=300, budget=300),
+    "first_token": dict(cid=1, n_ctx=1, budget=1, n_kv_heads=2, n_q_heads=8),
+}
+
+
+@pytest.mark.parametrize("name", list(APPEND_CASES))
+def test_step_with_append(fb, name):
+    """The new K/V row lands at position N - 1 of K, V and the packed planes, nothing else in the
+    caches changes, and the step's results are those of the oracle on the updated cache."""
+    from tests.gpu_util import Device, to_host
+    kw = dict(APPEND_CASES[name]); cid = kw.pop("cid")
+    w = W.WORKLOADS[cid].scaled(**kw)
+    x = W.make_inputs(w, n_cap=(w.n_ctx + 63) // 64 * 64)
+    print("append", name, flush=True)
+    d = Device(w, x)
+    d.pack()
+    a = W.make_append(w, x["fc_idx"], step=1, n_before=w.n_ctx - 1)
+    K, V = x["K"].copy(), x["V"].copy()
+    K[:, :, w.n_ctx - 1], V[:, :, w.n_ctx - 1] = a["k_new"], a["v_new"]
+    kp_before = to_host(d.Kp, d.st).copy()
+    run_step(fb, w, x, d=d, k_new=a["k_new"], v_new=a["v_new"], q=a["q"])
+    np.testing.assert_array_equal(to_host(d.K, d.st), K)
+    np.testing.assert_array_equal(to_host(d.V, d.st), V)
+    kp = to_host(d.Kp, d.st)
+    np.testing.assert_array_equal(kp[:, :, :, :w.n_ctx], O.pack_kcache(K, x["fc_idx"], w.n_ctx))
+    np.testing.assert_array_equal(kp[:, :, :, w.n_ctx:], kp_before[:, :, :, w.n_ctx:])
+    compare_step(w, a["q"], K, V, x["fc_idx"], d, w.n_ctx, w.budget)
+
+
 # ------------------------------------------------------------------------------------------------
 # full benchmark sizes, in the launch configuration the bench times
 # ------------------------------------------------------------------------------------------------
