@@ -321,6 +321,54 @@ def ragged(args, w, fb, W, np, torch):
     print(json.dumps(out), flush=True)
 
 
+def recall_table(args, w, fb, W, np, torch):
+    """Selection quality on the synthetic workload, in the form of the paper's compound contextual
+    agreement table (Sec. 3.3): for F dominant FCs and a top-K, the share of the full-head top-K set
+    (the paper's "Oracle" ranking, all d/2 FCs) that the F-FC scores recover.  Same kernels as the
+    decode step; averaged over KV heads and a few queries.  Not timed."""
+    half = w.head_dim // 2
+    x = W.make_inputs(w)
+    n_cap = x["n_cap"]
+    dev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+    tdt = torch.int16 if w.dtype == "bf16" else torch.float32
+    rows = w.batch * w.n_kv_heads
+    K = dev(x["K"])
+    queries = [dev(x["q"])] + [dev(W.make_append(w, x["fc_idx"], step=s, n_before=w.n_ctx - 1)["q"]) for s in range(1, 4)]
+    mk = lambda F, k: fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, F, w.n_ctx, n_cap, k, w.dtype)
+    ks = [k for k in (64, 256, 512, 1024, 2048) if k < w.n_ctx]
+    fs = sorted({max(1, w.n_fc // 4), max(1, w.n_fc // 2), (3 * w.n_fc) // 4, w.n_fc})
+    ws_bytes = max(fb.fasa_workspace_bytes(mk(half, k)) for k in ks)
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+    fb.fasa_workspace_init(mk(half, ks[0]), ws, ws_bytes)
+    S = torch.zeros((w.batch, w.n_kv_heads, n_cap), dtype=torch.float32, device="cuda")
+
+    def top_sets(fc_host, F, q):
+        fc = dev(np.ascontiguousarray(fc_host[:, :F]))
+        Kp = torch.zeros((w.batch, w.n_kv_heads, F, n_cap, 2), dtype=tdt, device="cuda")
+        fb.fasa_pack_kcache(mk(F, ks[0]), K, fc, Kp, 0, w.n_ctx)
+        fb.fasa_score(mk(F, ks[0]), q, Kp, fc, S)
+        out = {}
+        for k in ks:
+            T = torch.zeros((w.batch, w.n_kv_heads, k), dtype=torch.int32, device="cuda")
+            fb.fasa_topk(mk(F, k), S, T, ws, ws_bytes)
+            out[k] = T.cpu().numpy().reshape(rows, k)
+        return out
+
+    fc_all = np.tile(np.arange(half, dtype=np.int32), (w.n_kv_heads, 1))
+    table = {F: {k: 0.0 for k in ks} for F in fs}
+    for q in queries:
+        full = top_sets(fc_all, half, q)
+        for F in fs:
+            part = top_sets(x["fc_idx"], F, q)             # the first F of the head's dominant FCs
+            for k in ks:
+                table[F][k] += float(np.mean([len(np.intersect1d(full[k][r], part[k][r])) / k for r in range(rows)]))
+    table = {str(F): {str(k): round(v / len(queries), 4) for k, v in row.items()} for F, row in table.items()}
+    print(json.dumps({"metric": "top_k_recall_vs_full_head", "unit": "fraction", "n_gpus": 1, "data": "synthetic",
+                      "config": {"workload": w.name + "_recall_table", "n_ctx": w.n_ctx, "queries": len(queries),
+                                 "rows": "F (dominant FCs used)", "columns": "K (top-K size)"},
+                      "recall": table}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -342,6 +390,9 @@ def main():
     ap.add_argument("--ragged", type=int, default=0, metavar="STEPS",
                     help="serving loop: mixed sequence lengths growing by one per step, one captured graph "
                          "with the lengths on the device; use with --config 2")
+    ap.add_argument("--recall-table", action="store_true",
+                    help="selection quality only: recall of the full-head top-K set by F dominant FCs, for several "
+                         "F and K (the synthetic analogue of the paper's compound contextual agreement table)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only plain device copies of known size (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -378,6 +429,8 @@ def main():
         return calibrate(args, w, fb, W, np, torch)
     if args.ragged:
         return ragged(args, w, fb, W, np, torch)
+    if args.recall_table:
+        return recall_table(args, w, fb, W, np, torch)
     rows = w.batch * w.n_kv_heads
     model = W.algorithmic_bytes(w)
     bsel = min(w.budget, w.n_ctx)
