@@ -316,3 +316,19 @@ def test_full_size_sampled(fb, cid, rows):
     d = run_step(fb, w, x)
     n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget, rows=rows)
     print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
+
+
+def test_million_token_context(fb):
+    """A context of 2^20 + 77 tokens (one KV head, GQA 4): the longest rows the suite runs, past every
+    16-bit and 20-bit boundary of the token index, with a threshold bin of many thousand candidates."""
+    w = W.WORKLOADS[1].scaled(n_ctx=(1 << 20) + 77, budget=4096, n_kv_heads=1, n_q_heads=4, salient_frac=0.002)
+    x = W.make_inputs(w, n_cap=(w.n_ctx + 63) // 64 * 64)
+    print("million-token context", flush=True)
+    d = run_step(fb, w, x)
+    n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget)
+    print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
+    from tests.gpu_util import to_host
+    fb.fasa_dense_attend(d.shape, d.q, d.K, d.V, d.O, d.ws, d.ws_bytes)
+    torch.cuda.synchronize()
+    ref = O.dense_attend(x["q"], x["K"], x["V"], w.n_ctx)
+    assert np.abs(to_host(d.O) - ref).max() <= OUT_ATOL
