@@ -125,6 +125,35 @@ def rope_rotate_half(x: np.ndarray, pos: np.ndarray, base: float) -> np.ndarray:
     return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
 
 
+def rotate_half_to_interleaved(x: np.ndarray) -> np.ndarray:
+    """The same vectors in the other storage order of the rotation pairs: FC i moves from dims
+    (i, i + d/2) to dims (2i, 2i+1), the indexing of Sec. 3.1.  A pure permutation of the last axis."""
+    x = np.asarray(x)
+    half = x.shape[-1] // 2
+    out = np.empty_like(x)
+    out[..., 0::2] = x[..., :half]
+    out[..., 1::2] = x[..., half:]
+    return out
+
+
+def as_interleaved(x: dict) -> dict:
+    """A drawn input set (make_inputs / make_append) with q and the keys re-stored interleaved.
+    fc_idx keeps its meaning (FC numbers); V is untouched (its dim order carries no pairing)."""
+    out = dict(x)
+    for key in ("q", "K", "k_new", "q_pre"):
+        if key in out:
+            out[key] = rotate_half_to_interleaved(out[key])
+    return out
+
+
+def explicit_pairs(fc_idx: np.ndarray, d: int, interleaved: bool = False) -> np.ndarray:
+    """[Hkv][F][2] int32: the two head dims of every listed FC, written out (input of the
+    explicit-pair form of the dominant list)."""
+    fc = np.asarray(fc_idx, dtype=np.int32)
+    lo, hi = (2 * fc, 2 * fc + 1) if interleaved else (fc, fc + d // 2)
+    return np.stack([lo, hi], axis=-1).astype(np.int32)
+
+
 # ----------------------------------------------------------------------------------
 # the recipe
 # ----------------------------------------------------------------------------------
