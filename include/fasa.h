@@ -18,7 +18,8 @@
  *     first HIP call, so error paths work on a host without a GPU.  Inputs must be finite; the
  *     ranking of NaN scores is unspecified.
  *   - FC i of a d-dim head vector is the rotation pair (dim i, dim i + d/2) ("rotate-half"
- *     storage of the FC of paper Sec. 3.1); FCs are never split (paper App. D.2).
+ *     storage of the FC of paper Sec. 3.1) unless shape->pairing says otherwise (fasa_pairing
+ *     below); FCs are never split (paper App. D.2).
  *   - GQA: query head hq reads KV head hq / G, G = n_q_heads / n_kv_heads.  There is one score
  *     vector and one index set per KV head; scores are summed over the G query heads of the group.
  *   - Layouts (row-major, innermost last):
@@ -26,6 +27,7 @@
  *       K, V   [batch][n_kv_heads][>= n_ctx tokens][head_dim] dtype, element strides kv_stride_{b,h,n},
  *                                                            K holds post-RoPE keys
  *       fc_idx [n_kv_heads][n_fc]                           int32, distinct values in [0, head_dim/2)
+ *              ([n_kv_heads][n_fc][2], distinct dims in [0, head_dim), with FASA_PAIR_LIST)
  *       Kp     [batch][n_kv_heads][n_fc][n_cap][2]          dtype, FC-major copy of the dominant K dims
  *       S      [batch][n_kv_heads][n_cap]                   float32, entries >= n_ctx untouched
  *       T      [batch][n_kv_heads][min(budget, n_ctx)]      int32, a SET: order unspecified, no duplicates
@@ -53,6 +55,21 @@ typedef enum {
 
 typedef enum { FASA_BF16 = 0, FASA_F32 = 1 } fasa_dtype;
 
+/* Which two head dims entry f of a head's dominant list names (paper Sec. 3.1 defines an FC as a
+ * 2-D rotation subspace; where its two components are stored is a property of the model's weights):
+ *   FASA_PAIR_ROTATE_HALF  the entry is an FC number i, stored at dims (i, i + d/2);
+ *   FASA_PAIR_INTERLEAVED  the entry is an FC number i, stored at dims (2i, 2i + 1), the indexing
+ *                          Sec. 3.1 itself writes;
+ *   FASA_PAIR_LIST         the entry is the dim pair itself, fc_idx being [n_kv_heads][n_fc][2]: heads
+ *                          whose rotary encoding covers only part of the dims, or whose dominant
+ *                          components are single dims rather than rotation pairs (paper Sec. 6,
+ *                          partial-RoPE and ALiBi heads); any grouping of the listed dims into pairs
+ *                          gives the same scores.
+ * Every entry point that takes fc_idx reads it this way, the packed copy Kp holding
+ * (K[.., lo_f], K[.., hi_f]) per entry.  The memory-optimised variant, the calibration entry points
+ * and fasa_select_dominant_fcs work on FC numbers: they return FASA_EUNSUPPORTED for FASA_PAIR_LIST. */
+typedef enum { FASA_PAIR_ROTATE_HALF = 0, FASA_PAIR_INTERLEAVED = 1, FASA_PAIR_LIST = 2 } fasa_pairing;
+
 typedef struct fasa_shape {
   int32_t batch;       /* Bt                                                            */
   int32_t n_q_heads;   /* Hq                                                            */
@@ -63,7 +80,7 @@ typedef struct fasa_shape {
   int32_t n_cap;       /* token capacity of the Kp and S planes                         */
   int32_t budget;      /* B (paper: N_fac) >= 1; B >= N selects every token             */
   int32_t dtype;       /* fasa_dtype of q, K, V, Kp                                     */
-  int32_t reserved;    /* must be 0                                                     */
+  int32_t pairing;     /* fasa_pairing; 0 = rotate-half                                 */
   int64_t kv_stride_b; /* element strides of K and V; the head_dim stride is 1          */
   int64_t kv_stride_h;
   int64_t kv_stride_n;
@@ -84,20 +101,22 @@ int fasa_workspace_init(const fasa_shape* shape, void* ws, size_t ws_bytes, void
 
 /* Host-side check of a dominant-FC list (HOST pointer [n_kv_heads][n_fc]): every value in
  * [0, head_dim/2), no duplicates within a head (an FC is selected whole or not at all,
- * paper App. D.2). */
+ * paper App. D.2).  FASA_PAIR_LIST: [n_kv_heads][n_fc][2], every value in [0, head_dim), no dim
+ * twice within a head. */
 int fasa_validate_fc_idx(const fasa_shape* shape, const int32_t* fc_idx_host);
 
 /* Dominant-key cache maintenance (paper Alg. 2: Split + UpdateCache of k^dom).
  * For tokens n in [n_begin, n_end), 0 <= n_begin <= n_end <= n_cap:
  *     Kp[b,h,f,n,0] = K[b,h,n,i],  Kp[b,h,f,n,1] = K[b,h,n,i + d/2],  i = fc_idx[h,f]
- * A bit-exact copy.  Full pack after prefill: [0, N); append of one decoded token: [N-1, N).
+ * (the two dims shape->pairing names, in general).  A bit-exact copy.  Full pack after prefill: [0, N); append of one decoded token: [N-1, N).
  * shape->n_ctx and shape->budget are not used. */
 int fasa_pack_kcache(const fasa_shape* shape, const void* K, const int32_t* fc_idx, void* Kp,
                      int32_t n_begin, int32_t n_end, void* stream);
 
 /* TIP scoring (paper Sec. 4.1, S_t = sum over I_dom of single-FC scores; Alg. 2: q^dom (K^dom)^T):
  *     S[b,h,n] = sum_{g<G} sum_{f<F} ( q[b,hG+g,i_f] Kp[b,h,f,n,0] + q[b,hG+g,i_f+d/2] Kp[b,h,f,n,1] )
- * for n < n_ctx.  Raw logits: no 1/sqrt(d), no softmax.  float32 accumulation. */
+ * for n < n_ctx (i_f, i_f + d/2: in general the two dims shape->pairing names for entry f).
+ * Raw logits: no 1/sqrt(d), no softmax.  float32 accumulation. */
 int fasa_score(const fasa_shape* shape, const void* q, const void* Kp, const int32_t* fc_idx,
                float* S, void* stream);
 
@@ -214,7 +233,7 @@ int fasa_offload_decode_step(const fasa_shape* shape, const void* q, void* Kp, c
  * alpha = full-head raw scores, alpha^(i) = scores of FC i alone, both summed over the GQA group of
  * KV head h, ranked like fasa_topk (ties towards the lower index), K = min(top_k, n_ctx).
  *   Kp_all  DEVICE [batch][n_kv_heads][head_dim/2][n_cap][2]: fasa_pack_kcache with n_fc = head_dim/2
- *           and fc_idx[h] = 0, 1, .., head_dim/2 - 1
+ *           and fc_idx[h] = 0, 1, .., head_dim/2 - 1 (same shape->pairing as this call)
  *   CA_sum  DEVICE float [batch][n_kv_heads][head_dim/2]: the call ADDS this sample's CA to it, so a
  *           loop over samples leaves the sum; divide by the number of samples for the mean
  *   cws     DEVICE scratch of fasa_calibration_workspace_bytes(); needs no preparation

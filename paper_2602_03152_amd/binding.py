@@ -19,6 +19,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfasa.so
 
 FASA_OK, FASA_EINVAL, FASA_EUNSUPPORTED, FASA_EWORKSPACE, FASA_EHIP = 0, -1, -2, -3, -4
 FASA_BF16, FASA_F32 = 0, 1
+FASA_PAIR_ROTATE_HALF, FASA_PAIR_INTERLEAVED, FASA_PAIR_LIST = 0, 1, 2
 
 EXPORTS = [
     "fasa_workspace_bytes", "fasa_workspace_init", "fasa_validate_fc_idx", "fasa_pack_kcache", "fasa_score", "fasa_topk",
@@ -36,7 +37,7 @@ class FasaShape(C.Structure):
     _fields_ = [
         ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("n_fc", C.c_int32), ("n_ctx", C.c_int32), ("n_cap", C.c_int32), ("budget", C.c_int32),
-        ("dtype", C.c_int32), ("reserved", C.c_int32),
+        ("dtype", C.c_int32), ("pairing", C.c_int32),
         ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_n", C.c_int64),
     ]
 
@@ -104,13 +105,15 @@ lib = _lib   # raw handle, for tests of the C ABI itself
 
 
 def make_shape(batch, n_q_heads, n_kv_heads, head_dim, n_fc, n_ctx, n_cap, budget, dtype,
-               kv_stride_b=None, kv_stride_h=None, kv_stride_n=None) -> FasaShape:
-    """Shape struct; K/V strides default to a contiguous [batch][n_kv_heads][n_cap][head_dim] cache."""
+               kv_stride_b=None, kv_stride_h=None, kv_stride_n=None, pairing=0) -> FasaShape:
+    """Shape struct; K/V strides default to a contiguous [batch][n_kv_heads][n_cap][head_dim] cache.
+    pairing: FASA_PAIR_* or "half" | "interleaved" | "list"."""
     sn = head_dim if kv_stride_n is None else kv_stride_n
     sh = n_cap * sn if kv_stride_h is None else kv_stride_h
     sb = n_kv_heads * sh if kv_stride_b is None else kv_stride_b
     code = {"bf16": FASA_BF16, "f32": FASA_F32, FASA_BF16: FASA_BF16, FASA_F32: FASA_F32}[dtype]
-    return FasaShape(batch, n_q_heads, n_kv_heads, head_dim, n_fc, n_ctx, n_cap, budget, code, 0, sb, sh, sn)
+    pair = {"half": FASA_PAIR_ROTATE_HALF, "interleaved": FASA_PAIR_INTERLEAVED, "list": FASA_PAIR_LIST}.get(pairing, pairing)
+    return FasaShape(batch, n_q_heads, n_kv_heads, head_dim, n_fc, n_ctx, n_cap, budget, code, int(pair), sb, sh, sn)
 
 
 def _ptr(x) -> Optional[int]:

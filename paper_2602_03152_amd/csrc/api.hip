@@ -118,7 +118,8 @@ static int check_shape(const fasa_shape* s, unsigned need) {
   if (!s) return FASA_EINVAL;
   if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->head_dim < 2) return FASA_EINVAL;
   if (s->head_dim % 2 != 0 || s->n_q_heads % s->n_kv_heads != 0) return FASA_EINVAL;
-  if (s->reserved != 0) return FASA_EINVAL;
+  if (s->pairing != FASA_PAIR_ROTATE_HALF && s->pairing != FASA_PAIR_INTERLEAVED && s->pairing != FASA_PAIR_LIST)
+    return FASA_EINVAL;
   if (s->dtype != FASA_BF16 && s->dtype != FASA_F32) return FASA_EINVAL;
   if (s->n_cap < 1 || s->n_cap % 64 != 0) return FASA_EINVAL;
   if ((long long)s->batch * s->n_kv_heads > 65535) return FASA_EUNSUPPORTED;
@@ -186,13 +187,16 @@ int fasa_validate_fc_idx(const fasa_shape* shape, const int32_t* fc_idx_host) {
   int rc = check_shape(shape, kNeedFc);
   if (rc != FASA_OK) return rc;
   if (!fc_idx_host) return FASA_EINVAL;
-  const int half = shape->head_dim / 2;
+  // FC numbers in [0, d/2), or (explicit pairs) 2 n_fc dims in [0, d); nothing twice within a head
+  const bool pairs = shape->pairing == FASA_PAIR_LIST;
+  const int limit = pairs ? shape->head_dim : shape->head_dim / 2;
+  const int words = pairs ? 2 * shape->n_fc : shape->n_fc;
+  if (limit > 4096) return FASA_EUNSUPPORTED;
   for (int h = 0; h < shape->n_kv_heads; ++h) {
     bool seen[4096] = {false};
-    if (half > 4096) return FASA_EUNSUPPORTED;
-    for (int f = 0; f < shape->n_fc; ++f) {
-      const int i = fc_idx_host[h * shape->n_fc + f];
-      if (i < 0 || i >= half || seen[i]) return FASA_EINVAL;
+    for (int f = 0; f < words; ++f) {
+      const int i = fc_idx_host[h * words + f];
+      if (i < 0 || i >= limit || seen[i]) return FASA_EINVAL;
       seen[i] = true;
     }
   }
@@ -353,7 +357,7 @@ int fasa_decode_step_paged(const fasa_shape* shape, const fasa_paging* paging, c
 }
 
 size_t fasa_offload_stage_bytes(const fasa_shape* shape) {
-  if (check_shape(shape, kNeedCtx | kNeedBudget) != FASA_OK) return 0;
+  if (check_shape(shape, kNeedCtx | kNeedBudget) != FASA_OK || shape->pairing == FASA_PAIR_LIST) return 0;
   const size_t e = shape->dtype == FASA_BF16 ? 2 : 4;
   const size_t bsel = (size_t)(shape->budget < shape->n_ctx ? shape->budget : shape->n_ctx);
   return align256(2 * (size_t)shape->batch * shape->n_kv_heads * bsel * shape->head_dim * e);
@@ -363,6 +367,7 @@ int fasa_offload_split_kcache(const fasa_shape* shape, const void* K, const int3
                               void* Knd_host, int32_t n_begin, int32_t n_end, void* stream) {
   int rc = check_shape(shape, kNeedFc | kNeedStrides);
   if (rc != FASA_OK) return rc;
+  if (shape->pairing == FASA_PAIR_LIST) return FASA_EUNSUPPORTED;   // the split works on FC numbers
   if (!K || !fc_idx || !Kp || !Knd_host) return FASA_EINVAL;
   if (!aligned16(K) || !aligned16(Kp) || !aligned16(fc_idx) || !aligned16(Knd_host)) return FASA_EINVAL;
   if (n_begin < 0 || n_end < n_begin || n_end > shape->n_cap) return FASA_EINVAL;
@@ -377,6 +382,7 @@ int fasa_offload_decode_step(const fasa_shape* shape, const void* q, void* Kp, c
                              size_t stage_bytes, void* stream) {
   int rc = check_shape(shape, kNeedCtx | kNeedBudget | kNeedFc | kNeedStrides);
   if (rc != FASA_OK) return rc;
+  if (shape->pairing == FASA_PAIR_LIST) return FASA_EUNSUPPORTED;
   if (!q || !Kp || !fc_idx || !Knd_host || !V_host || !S || !T || !O || !stage) return FASA_EINVAL;
   if ((k_new == nullptr) != (v_new == nullptr)) return FASA_EINVAL;
   if (!aligned16(q) || !aligned16(Kp) || !aligned16(fc_idx) || !aligned16(Knd_host) || !aligned16(V_host) ||
@@ -425,6 +431,7 @@ int calib_layout(const fasa_shape* shape, int32_t top_k, CalibLayout* L) {
   int rc = check_shape(shape, kNeedCtx);
   if (rc != FASA_OK) return rc;
   if (top_k < 1) return FASA_EINVAL;
+  if (shape->pairing == FASA_PAIR_LIST) return FASA_EUNSUPPORTED;   // agreement is defined per FC number
   const int half = shape->head_dim / 2;
   if ((long long)shape->batch * shape->n_kv_heads * half > 65535) return FASA_EUNSUPPORTED;
   if (shape->n_ctx > calib_max_ctx()) return FASA_EUNSUPPORTED;
@@ -504,6 +511,7 @@ int fasa_contextual_agreement(const fasa_shape* shape, const void* q, const void
 int fasa_select_dominant_fcs(const fasa_shape* shape, const float* ca_mean_host, int32_t* fc_idx_host_out) {
   int rc = check_shape(shape, kNeedFc);
   if (rc != FASA_OK) return rc;
+  if (shape->pairing == FASA_PAIR_LIST) return FASA_EUNSUPPORTED;
   if (!ca_mean_host || !fc_idx_host_out) return FASA_EINVAL;
   const int half = shape->head_dim / 2;
   for (int h = 0; h < shape->n_kv_heads; ++h) {
@@ -520,7 +528,7 @@ const char* fasa_strerror(int status) {
   switch (status) {
     case FASA_OK: return "ok";
     case FASA_EINVAL: return "invalid argument (null or misaligned pointer, bad shape or index list)";
-    case FASA_EUNSUPPORTED: return "shape outside what the kernels support (head_dim must be 128, GQA group <= 8)";
+    case FASA_EUNSUPPORTED: return "request outside what the kernels support (head_dim must be 128, GQA group <= 8, explicit dim pairs only for packing, scoring and the decode steps)";
     case FASA_EWORKSPACE: return "workspace smaller than fasa_workspace_bytes()";
     case FASA_EHIP: return "HIP call failed (see fasa_last_hip_error)";
     default: return "unknown status";

@@ -67,6 +67,24 @@ __device__ __forceinline__ long long kv_row_offset(const PageMap& pm, int b, int
   return (long long)(slot >> pm.shift) * sb + (long long)(slot & ((1 << pm.shift) - 1)) * sn;
 }
 
+// The two head dims that entry f of KV head h's dominant list names, as lo | hi << 8.  The list
+// holds FC numbers (one word per entry) or, for FASA_PAIR_LIST, the dim pairs themselves (two
+// words).  Values are clamped into the head: a stray entry can never become a stray LDS index.
+__device__ __forceinline__ int list_word(int pairing, int F, int h, int f, int which) {
+  return pairing == FASA_PAIR_LIST ? (h * F + f) * 2 + which : h * F + f;
+}
+__device__ __forceinline__ int pair_dims(int pairing, int a, int b) {
+  constexpr int D = kHeadDim;
+  const int i = min(max(a, 0), D / 2 - 1);
+  int lo = pairing == FASA_PAIR_INTERLEAVED ? 2 * i : i;
+  int hi = pairing == FASA_PAIR_INTERLEAVED ? 2 * i + 1 : i + D / 2;
+  if (pairing == FASA_PAIR_LIST) {
+    lo = min(max(a, 0), D - 1);
+    hi = min(max(b, 0), D - 1);
+  }
+  return lo | (hi << 8);
+}
+
 // Workspace carve-up (all offsets 256-byte aligned).
 struct WsLayout {
   size_t hist_off, ctl_off, cand_off, part_acc_off, part_ml_off, tslot_off, total;

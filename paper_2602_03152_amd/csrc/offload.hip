@@ -13,18 +13,19 @@ constexpr int kOffTile = 64;   // tokens per workgroup of the split kernel
 
 // Where output dim j of a rebuilt key row comes from: bit 15 set -> dominant pair entry
 // (f * 2 + which), else index into the row's non-dominant part.
-__device__ __forceinline__ void build_dim_map(const int32_t* __restrict__ fc_idx_h, int F,
+__device__ __forceinline__ void build_dim_map(const int32_t* __restrict__ fc_idx_h, int F, int pairing,
                                               uint16_t* src /*[D]*/, uint8_t* is_dom /*[D]*/) {
   constexpr int D = kHeadDim;
   const int t = threadIdx.x;
   if (t < D) is_dom[t] = 0;
   __syncthreads();
   if (t < F) {
-    const int i = fc_idx_h[t];
-    is_dom[i] = 1;
-    is_dom[i + D / 2] = 1;
-    src[i] = (uint16_t)(0x8000u | (uint32_t)(2 * t));
-    src[i + D / 2] = (uint16_t)(0x8000u | (uint32_t)(2 * t + 1));
+    const int pr = pair_dims(pairing, fc_idx_h[t], 0);   // FC numbers only (rotate-half or interleaved)
+    const int lo = pr & 255, hi = pr >> 8;
+    is_dom[lo] = 1;
+    is_dom[hi] = 1;
+    src[lo] = (uint16_t)(0x8000u | (uint32_t)(2 * t));
+    src[hi] = (uint16_t)(0x8000u | (uint32_t)(2 * t + 1));
   }
   __syncthreads();
   if (t < D && !is_dom[t]) {
@@ -42,7 +43,8 @@ __global__ __launch_bounds__(256) void offload_split_kernel(const ET* __restrict
                                                             ET* __restrict__ Kp,
                                                             ET* __restrict__ Knd, int Hkv, int F,
                                                             int n_cap, int n_begin, int n_end,
-                                                            long long sb, long long sh, long long sn) {
+                                                            long long sb, long long sh, long long sn,
+                                                            int pairing) {
   constexpr int D = kHeadDim;
   constexpr int PITCH = D + 16 / sizeof(ET);
   __shared__ __align__(16) ET tile[kOffTile][PITCH];
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(256) void offload_split_kernel(const ET* __restrict
   const int n0 = n_begin + blockIdx.x * kOffTile;
   const int nt = min(kOffTile, n_end - n0);
   const int t = threadIdx.x;
-  build_dim_map(fc_idx + h * F, F, src, is_dom);
+  build_dim_map(fc_idx + h * F, F, pairing, src, is_dom);
 
   constexpr int VEC = 16 / sizeof(ET);
   constexpr int LPR = D / VEC;
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(256) void offload_append_kernel(ET* __restrict__ Kp
                                                              const ET* __restrict__ k_new,
                                                              const ET* __restrict__ v_new, int Hkv,
                                                              int F, int n_cap, int n_ctx, long long sb,
-                                                             long long sh, long long sn) {
+                                                             long long sh, long long sn, int pairing) {
   constexpr int D = kHeadDim;
   __shared__ uint16_t src[D];
   __shared__ uint8_t is_dom[D];
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(256) void offload_append_kernel(ET* __restrict__ Kp
   const int b = row / Hkv, h = row % Hkv;
   const int t = threadIdx.x;
   const int n = n_ctx - 1;
-  build_dim_map(fc_idx + h * F, F, src, is_dom);
+  build_dim_map(fc_idx + h * F, F, pairing, src, is_dom);
   const int nd = D - 2 * F;
   if (t < D) {
     const ET v = k_new[(size_t)row * D + t];
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(256) void offload_gather_kernel(const ET* __restric
                                                              ET* __restrict__ KT, ET* __restrict__ VT,
                                                              int Hkv, int F, int n_cap, int n_ctx,
                                                              int count, long long sb, long long sh,
-                                                             long long sn) {
+                                                             long long sn, int pairing) {
   constexpr int D = kHeadDim;
   constexpr int VEC = 16 / sizeof(ET);
   constexpr int LPR = D / VEC;
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(256) void offload_gather_kernel(const ET* __restric
   const int nt = min(TOK, count - j0);
   const int t = threadIdx.x;
   if (t < nt) toks[t] = min(max(T[(size_t)row * count + j0 + t], 0), n_ctx - 1);
-  build_dim_map(fc_idx + h * F, F, src, is_dom);   // contains barriers: toks is visible after it
+  build_dim_map(fc_idx + h * F, F, pairing, src, is_dom);   // contains barriers: toks is visible after it
 
   const int nd = D - 2 * F;
   const ET* knd = Knd + (long long)row * n_cap * nd;
@@ -180,10 +182,10 @@ hipError_t launch_offload_split(const fasa_shape& s, const void* K, const int32_
     return launch("fasa_offload_split", offload_split_kernel<uint16_t>, grid, block, st,
                   (const uint16_t*)K, fc_idx, (uint16_t*)Kp, (uint16_t*)Knd, s.n_kv_heads, s.n_fc,
                   s.n_cap, n_begin, n_end, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                  (long long)s.kv_stride_n);
+                  (long long)s.kv_stride_n, s.pairing);
   return launch("fasa_offload_split", offload_split_kernel<float>, grid, block, st, (const float*)K,
                 fc_idx, (float*)Kp, (float*)Knd, s.n_kv_heads, s.n_fc, s.n_cap, n_begin, n_end,
-                (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+                (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n, s.pairing);
 }
 
 hipError_t launch_offload_append(const fasa_shape& s, void* Kp, void* Knd, void* Vh,
@@ -194,11 +196,11 @@ hipError_t launch_offload_append(const fasa_shape& s, void* Kp, void* Knd, void*
     return launch("fasa_offload_append", offload_append_kernel<uint16_t>, dim3(rows), dim3(256), st,
                   (uint16_t*)Kp, (uint16_t*)Knd, (uint16_t*)Vh, fc_idx, (const uint16_t*)k_new,
                   (const uint16_t*)v_new, s.n_kv_heads, s.n_fc, s.n_cap, s.n_ctx,
-                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n, s.pairing);
   return launch("fasa_offload_append", offload_append_kernel<float>, dim3(rows), dim3(256), st,
                 (float*)Kp, (float*)Knd, (float*)Vh, fc_idx, (const float*)k_new, (const float*)v_new,
                 s.n_kv_heads, s.n_fc, s.n_cap, s.n_ctx, (long long)s.kv_stride_b,
-                (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+                (long long)s.kv_stride_h, (long long)s.kv_stride_n, s.pairing);
 }
 
 hipError_t launch_offload_gather(const fasa_shape& s, const void* Kp, const void* Knd, const void* Vh,
@@ -211,13 +213,13 @@ hipError_t launch_offload_gather(const fasa_shape& s, const void* Kp, const void
     return launch("fasa_offload_gather", offload_gather_kernel<uint16_t>, grid, block, st,
                   (const uint16_t*)Kp, (const uint16_t*)Knd, (const uint16_t*)Vh, fc_idx, T,
                   (uint16_t*)KT, (uint16_t*)VT, s.n_kv_heads, s.n_fc, s.n_cap, s.n_ctx, count,
-                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n);
+                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n, s.pairing);
   }
   dim3 grid((count + 7) / 8, rows), block(256);
   return launch("fasa_offload_gather", offload_gather_kernel<float>, grid, block, st, (const float*)Kp,
                 (const float*)Knd, (const float*)Vh, fc_idx, T, (float*)KT, (float*)VT, s.n_kv_heads,
                 s.n_fc, s.n_cap, s.n_ctx, count, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                (long long)s.kv_stride_n);
+                (long long)s.kv_stride_n, s.pairing);
 }
 
 }  // namespace fasa

@@ -17,7 +17,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const ET* __restrict__ K,
                                                    const int32_t* __restrict__ fc_idx,
                                                    ET* __restrict__ Kp, int Hkv, int F, int n_cap,
                                                    int n_begin, int n_end, long long sb,
-                                                   long long sh, long long sn, PageMap pm) {
+                                                   long long sh, long long sn, PageMap pm,
+                                                   int pairing) {
   constexpr int D = kHeadDim;
   constexpr int PITCH = D + 16 / sizeof(ET);  // keeps 16-byte alignment, staggers LDS banks
   __shared__ __align__(16) ET tile[kPackTile][PITCH];
@@ -29,7 +30,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const ET* __restrict__ K,
   const int nt = min(kPackTile, n_end - n0);
   const int t = threadIdx.x;
 
-  if (t < F) fcs[t] = fc_idx[h * F + t];
+  if (t < F)
+    fcs[t] = pair_dims(pairing, fc_idx[list_word(pairing, F, h, t, 0)], fc_idx[list_word(pairing, F, h, t, 1)]);
 
   constexpr int VEC = 16 / sizeof(ET);    // elements per 16-byte load
   constexpr int LPR = D / VEC;            // lanes per row
@@ -45,10 +47,10 @@ __global__ __launch_bounds__(256) void pack_kernel(const ET* __restrict__ K,
   for (int i = t; i < F * kPackTile; i += 256) {
     const int f = i / kPackTile, r = i % kPackTile;
     if (r < nt) {
-      const int d0 = fcs[f];
+      const int pr = fcs[f];
       ET* o = dst + ((long long)f * n_cap + (n0 + r)) * 2;
-      o[0] = tile[r][d0];
-      o[1] = tile[r][d0 + D / 2];
+      o[0] = tile[r][pr & 255];
+      o[1] = tile[r][pr >> 8];
     }
   }
 }
@@ -60,10 +62,10 @@ hipError_t launch_pack(const fasa_shape& s, const void* K, const int32_t* fc_idx
   if (s.dtype == FASA_BF16)
     return launch("fasa_pack", pack_kernel<uint16_t>, grid, block, st, (const uint16_t*)K, fc_idx,
                   (uint16_t*)Kp, s.n_kv_heads, s.n_fc, s.n_cap, n_begin, n_end,
-                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n, pm);
+                  (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n, pm, s.pairing);
   return launch("fasa_pack", pack_kernel<float>, grid, block, st, (const float*)K, fc_idx,
                 (float*)Kp, s.n_kv_heads, s.n_fc, s.n_cap, n_begin, n_end,
-                (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n, pm);
+                (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n, pm, s.pairing);
 }
 
 }  // namespace fasa

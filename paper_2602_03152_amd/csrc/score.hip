@@ -38,7 +38,7 @@ constexpr int kScoreFB = 16;  // FC planes in flight per thread
 // them, and a wait for an earlier load is only cheap if the loads after it are unconditional.  Order
 // of issue, all of it branch-free and by every lane (so that nothing can be moved into a test):
 //   1. this lane's column of the group's query heads (lane t: head dim t mod 128, up to 8 heads)
-//      and one entry of the head's dominant-FC list; neither depends on the other;
+//      and one entry (one or two words) of the head's dominant list; neither depends on the other;
 //   2. the K planes (lanes beyond the row's length re-read its first tokens);
 //   3. wait for 1 only: group sum per head dim -> LDS, then lanes < F pick their FC's two
 //      components.  This and the LDS clearing run under the latency of 2.
@@ -49,7 +49,10 @@ constexpr int kScoreFB = 16;  // FC planes in flight per thread
 // through LDS, lanes < F extract their FC's pair from it, the workgroup whose slice holds token
 // N - 1 writes the pairs to the Kp planes and the whole row to K and V, and the one thread that owns
 // the token replaces, in its registers, what it loaded from the (not yet written) planes.
-template <typename ET, bool HIST, int NB, bool APPEND>
+//
+// PAIR (a fasa_pairing): the list holds FC numbers i, stored at dims (i, i + d/2) or (2i, 2i + 1),
+// or explicit dim pairs (two words per entry).
+template <typename ET, bool HIST, int NB, bool APPEND, int PAIR>
 __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET* Kp,
                                                     const int32_t* __restrict__ fc_idx,
                                                     float* __restrict__ S,
@@ -63,8 +66,11 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
   constexpr int D = kHeadDim;
   constexpr int TPT = ScoreTraits<ET>::TPT;
   constexpr int NW = NB ? NB * 8 : kScoreFB;
+  constexpr bool PAIRS = PAIR == FASA_PAIR_LIST;
+  constexpr int PAIR_SHIFT = PAIR == FASA_PAIR_INTERLEAVED ? 1 : 0;       // FC number -> first dim
+  constexpr int PAIR_ADD = PAIR == FASA_PAIR_INTERLEAVED ? 1 : D / 2;     // first dim -> second dim
   __shared__ float qsum[256];      // [t]: sum over the group of q[., t mod 128] (upper half: copies)
-  __shared__ int32_t fcl[256];     // [t]: fc_idx[h][min(t, F - 1)]
+  __shared__ int32_t fcl[256];     // [t]: dims of list entry min(t, F - 1): lo (PAIRS: lo | hi << 8)
   __shared__ float2 qs[D / 2];
   __shared__ uint32_t lh[HIST ? kHistBins : 1];
   __shared__ ET knew[APPEND ? D : 1];          // the new key row
@@ -83,7 +89,10 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
   ET qcol[kMaxGroup];
 #pragma unroll
   for (int g = 0; g < kMaxGroup; ++g) qcol[g] = qh[(size_t)min(g, G - 1) * D];   // beyond the group: its last head, not added
-  const int32_t fci = fc_idx[h * F + min(t, F - 1)];
+  const int fe = h * F + min(t, F - 1);
+  const int32_t fci = fc_idx[PAIRS ? 2 * fe : fe];
+  int32_t fcj = 0;
+  if constexpr (PAIRS) fcj = fc_idx[2 * fe + 1];
   ET newkv = ET(0);
   if constexpr (APPEND) newkv = (t < D ? k_new : v_new)[(size_t)row * D + (t & (D - 1))];
   // the appended token: which workgroup and thread own it, and which of the thread's tokens it is
@@ -114,7 +123,9 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
       sum += g < G ? a : 0.f;
     }
     qsum[t] = sum;
-    fcl[t] = min(max(fci, 0), D / 2 - 1);   // LDS indices below stay in range whatever the list holds
+    // LDS indices below stay in range whatever the list holds
+    if constexpr (PAIRS) fcl[t] = min(max(fci, 0), D - 1) | (min(max(fcj, 0), D - 1) << 8);
+    else fcl[t] = min(max(fci, 0), D / 2 - 1) << PAIR_SHIFT;
     if constexpr (APPEND) {
       if (t < D) knew[t] = newkv;
     }
@@ -124,10 +135,11 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
   }
   __syncthreads();
   if (t < F) {
-    const int i = fcl[t];
-    qs[t] = make_float2(qsum[i], qsum[i + D / 2]);
+    const int dl = PAIRS ? fcl[t] & 255 : fcl[t];
+    const int dh = PAIRS ? fcl[t] >> 8 : dl + PAIR_ADD;
+    qs[t] = make_float2(qsum[dl], qsum[dh]);
     if constexpr (APPEND) {
-      const ET lo = knew[i], hi = knew[i + D / 2];
+      const ET lo = knew[dl], hi = knew[dh];
       if constexpr (sizeof(ET) == 2) kpair[t] = make_uint2((uint32_t)lo | ((uint32_t)hi << 16), 0u);
       else kpair[t] = make_uint2(__float_as_uint(lo), __float_as_uint(hi));
       if (own_wg) {
@@ -261,30 +273,44 @@ __global__ __launch_bounds__(256) void hist_kernel(const float* __restrict__ S,
     if (c[k]) atomicAdd(&gh[t + 256 * k], c[k]);
 }
 
-template <typename ET, bool HIST, int NB, bool APPEND>
+template <typename ET, bool HIST, int NB, bool APPEND, int PAIR>
 static hipError_t launch_score_v(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
                                  float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
                                  const AppendArgs& ap) {
   const int rows = s.batch * s.n_kv_heads;
   const int per_block = 256 * ScoreTraits<ET>::TPT;
   const int nslices = (s.n_ctx + per_block - 1) / per_block;
-  return launch(HIST ? "fasa_score_hist" : "fasa_score", score_kernel<ET, HIST, NB, APPEND>,
+  return launch(HIST ? "fasa_score_hist" : "fasa_score", score_kernel<ET, HIST, NB, APPEND, PAIR>,
                 dim3(rows * nslices), dim3(256), st, (const ET*)q, (ET*)Kp, fc_idx, S, hist, rows, nslices,
                 s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap, rl.n_ctx, (const ET*)ap.k_new,
                 (const ET*)ap.v_new, (ET*)ap.K, (ET*)ap.V, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
                 (long long)s.kv_stride_n, ap.pm);
 }
 
+template <typename ET, bool HIST, bool APPEND, int PAIR>
+static hipError_t launch_score_f(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
+                                 float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
+                                 const AppendArgs& ap) {
+  switch (s.n_fc) {   // the usual settings (an eighth to a half of the FCs) get straight-line loads
+    case 8: return launch_score_v<ET, HIST, 1, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    case 16: return launch_score_v<ET, HIST, 2, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    case 24: return launch_score_v<ET, HIST, 3, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    case 32: return launch_score_v<ET, HIST, 4, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    default: return launch_score_v<ET, HIST, 0, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+  }
+}
+
 template <typename ET, bool HIST, bool APPEND>
 static hipError_t launch_score_h(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
                                  float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
                                  const AppendArgs& ap) {
-  switch (s.n_fc) {   // the usual settings (an eighth to a half of the FCs) get straight-line loads
-    case 8: return launch_score_v<ET, HIST, 1, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
-    case 16: return launch_score_v<ET, HIST, 2, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
-    case 24: return launch_score_v<ET, HIST, 3, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
-    case 32: return launch_score_v<ET, HIST, 4, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
-    default: return launch_score_v<ET, HIST, 0, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+  switch (s.pairing) {
+    case FASA_PAIR_INTERLEAVED:
+      return launch_score_f<ET, HIST, APPEND, FASA_PAIR_INTERLEAVED>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    case FASA_PAIR_LIST:   // explicit dim pairs: the any-F kernel only
+      return launch_score_v<ET, HIST, 0, APPEND, FASA_PAIR_LIST>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    default:
+      return launch_score_f<ET, HIST, APPEND, FASA_PAIR_ROTATE_HALF>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
   }
 }
 

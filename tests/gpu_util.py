@@ -28,8 +28,9 @@ def to_host(t: torch.Tensor, like: np.dtype = None) -> np.ndarray:
 class Device:
     """Device-side buffers of one workload (inputs from the generator, outputs zero/garbage filled)."""
 
-    def __init__(self, w, x, n_cap=None, poison=True):
+    def __init__(self, w, x, n_cap=None, poison=True, pairing="half"):
         self.w = w
+        self.pairing = pairing      # how x["fc_idx"] names head dims ("half" | "interleaved" | "list")
         self.n_cap = x["n_cap"] if n_cap is None else n_cap
         assert self.n_cap % 64 == 0
         self.st = np.uint16 if w.dtype == "bf16" else np.float32
@@ -56,7 +57,7 @@ class Device:
         w = self.w
         return fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_fc,
                              w.n_ctx if n_ctx is None else n_ctx, self.n_cap,
-                             w.budget if budget is None else budget, w.dtype)
+                             w.budget if budget is None else budget, w.dtype, pairing=self.pairing)
 
     def pack(self, n_begin=0, n_end=None):
         fb.fasa_pack_kcache(self.shape, self.K, self.fc_idx, self.Kp, n_begin,

@@ -95,9 +95,38 @@ def test_decode_step_rejects_bad_shapes(kw, code):
     assert rc == code
 
 
-def test_reserved_field_must_be_zero():
-    s = _shape(); s.reserved = 1
-    assert fb.lib.fasa_score(C.byref(s), A, A, A, A, None) == fb.FASA_EINVAL
+def test_pairing_field_is_validated():
+    for bad in (3, -1, 1 << 20):
+        s = _shape(); s.pairing = bad
+        assert fb.lib.fasa_score(C.byref(s), A, A, A, A, None) == fb.FASA_EINVAL
+        assert fb.fasa_workspace_bytes(s) == 0
+
+
+def test_validate_explicit_pair_list():
+    s = _shape(n_fc=3); s.pairing = fb.FASA_PAIR_LIST
+    ok = np.tile(np.array([[0, 127], [64, 5], [17, 3]], np.int32), (8, 1, 1))
+    fb.fasa_validate_fc_idx(s, ok)
+    for bad in ([[0, 128], [64, 5], [17, 3]], [[0, -1], [64, 5], [17, 3]], [[0, 127], [64, 0], [17, 3]]):
+        arr = ok.copy(); arr[5] = bad
+        with pytest.raises(fb.FasaError) as e:
+            fb.fasa_validate_fc_idx(s, arr)
+        assert e.value.status == fb.FASA_EINVAL
+    # FC numbers: the interleaved pairing takes the same lists as rotate-half
+    s = _shape(n_fc=4); s.pairing = fb.FASA_PAIR_INTERLEAVED
+    fb.fasa_validate_fc_idx(s, np.tile(np.array([0, 63, 5, 17], np.int32), (8, 1)))
+
+
+def test_fc_number_entry_points_refuse_explicit_pairs():
+    s = _shape(); s.pairing = fb.FASA_PAIR_LIST
+    L = fb.lib
+    assert fb.fasa_offload_stage_bytes(s) == 0
+    assert L.fasa_offload_split_kcache(C.byref(s), A, A, A, A, 0, 10, None) == fb.FASA_EUNSUPPORTED
+    assert L.fasa_offload_decode_step(C.byref(s), A, A, A, A, A, None, None, A, A, A, A, 1 << 40, A, 1 << 40,
+                                      None) == fb.FASA_EUNSUPPORTED
+    assert fb.fasa_calibration_workspace_bytes(s, 64) == 0
+    assert L.fasa_contextual_agreement(C.byref(s), A, A, 64, A, A, 1 << 40, None) == fb.FASA_EUNSUPPORTED
+    ca = np.zeros((8, 64), np.float32); out = np.zeros((8, 16), np.int32)
+    assert L.fasa_select_dominant_fcs(C.byref(s), ca.ctypes.data, out.ctypes.data) == fb.FASA_EUNSUPPORTED
 
 
 def test_null_and_misaligned_pointers():

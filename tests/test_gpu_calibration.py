@@ -16,12 +16,13 @@ def fb():
     return binding
 
 
-def _calibrate(fb, w, x, queries, top_k):
+def _calibrate(fb, w, x, queries, top_k, pairing="half"):
     from tests.gpu_util import to_dev
     half = w.head_dim // 2
     n_cap = x["n_cap"]
     tdt = torch.int16 if w.dtype == "bf16" else torch.float32
-    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, half, w.n_ctx, n_cap, top_k, w.dtype)
+    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, half, w.n_ctx, n_cap, top_k, w.dtype,
+                          pairing=pairing)
     K = to_dev(x["K"])
     fc_all = torch.arange(half, dtype=torch.int32, device="cuda").repeat(w.n_kv_heads, 1).contiguous()
     Kp_all = torch.zeros((w.batch, w.n_kv_heads, half, n_cap, 2), dtype=tdt, device="cuda")
@@ -56,6 +57,23 @@ def test_contextual_agreement_matches_oracle(fb, name, kw, top_k):
     assert np.abs(got * kk - cnt_got).max() < 1e-3
     assert np.abs(cnt_got - cnt_ref).max() <= 4, int(np.abs(cnt_got - cnt_ref).max())
     print("  exact counts on %.1f %% of (head, FC) pairs" % (100 * (cnt_got == cnt_ref).mean()), flush=True)
+    assert (cnt_got == cnt_ref).mean() > 0.9
+
+
+def test_contextual_agreement_interleaved_storage(fb):
+    """The same vectors stored with FC i at dims (2i, 2i+1): the agreement of FC i is what it was
+    (the device's float32 scores are even bit-identical, the FC's two products being added in the
+    same order), and it matches the oracle reading the interleaved storage."""
+    w = W.WORKLOADS[1].scaled(n_ctx=900 + 7, budget=64, n_kv_heads=2, n_q_heads=8)
+    x = W.make_inputs(w, n_cap=(w.n_ctx + 63) // 64 * 64)
+    xi = W.as_interleaved(x)
+    print("calibration interleaved", flush=True)
+    got_half = _calibrate(fb, w, x, [x["q"]], 80)
+    got = _calibrate(fb, w, xi, [xi["q"]], 80, pairing="interleaved")
+    np.testing.assert_array_equal(got, got_half)
+    ref = O.contextual_agreement(xi["q"], xi["K"], w.n_ctx, 80, pairing="interleaved")
+    cnt_got, cnt_ref = np.rint(got * 80).astype(int), np.rint(ref * 80).astype(int)
+    assert np.abs(cnt_got - cnt_ref).max() <= 4
     assert (cnt_got == cnt_ref).mean() > 0.9
 
 

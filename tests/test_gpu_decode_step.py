@@ -45,10 +45,10 @@ def check_selection(S_ref, D_ref, T_gpu, budget, n_ctx):
     return n_diff
 
 
-def run_step(fb, w, x, d=None, k_new=None, v_new=None, q=None, n_ctx=None, budget=None):
+def run_step(fb, w, x, d=None, k_new=None, v_new=None, q=None, n_ctx=None, budget=None, pairing="half"):
     from tests.gpu_util import Device, to_dev
     if d is None:
-        d = Device(w, x)
+        d = Device(w, x, pairing=pairing)
         d.pack()
     shape = d.make_shape(n_ctx=n_ctx, budget=budget)
     qd = d.q if q is None else to_dev(q)
@@ -59,13 +59,13 @@ def run_step(fb, w, x, d=None, k_new=None, v_new=None, q=None, n_ctx=None, budge
     return d
 
 
-def compare_step(w, x_host_q, K, V, fc_idx, d, n_ctx, budget, rows=None):
+def compare_step(w, x_host_q, K, V, fc_idx, d, n_ctx, budget, rows=None, pairing="half"):
     """Oracle vs device outputs for the (sub)set of batch entries `rows`."""
     from tests.gpu_util import to_host
     bsel = min(budget, n_ctx)
     bs = list(range(w.batch)) if rows is None else rows
     q = x_host_q[bs]
-    S_ref, D_ref = O.score(q, K[bs], fc_idx, n_ctx)
+    S_ref, D_ref = O.score(q, K[bs], fc_idx, n_ctx, pairing)
     S = to_host(d.S)[bs][:, :, :n_ctx].astype(np.float64)
     err = np.abs(S - S_ref)
     assert np.all(err <= SCORE_RTOL * np.maximum(np.abs(S_ref), D_ref))

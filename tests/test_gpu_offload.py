@@ -33,15 +33,18 @@ CASES = {
 }
 
 
-@pytest.mark.parametrize("name", list(CASES))
-def test_offload_step_matches_oracle_and_on_device_variant(fb, name):
+@pytest.mark.parametrize("name,pairing", [(n, "half") for n in CASES] +
+                         [("cfg1_ragged", "interleaved"), ("odd_f5", "interleaved"), ("cfg0_f32", "interleaved")])
+def test_offload_step_matches_oracle_and_on_device_variant(fb, name, pairing):
     from tests.gpu_util import Device, to_host, to_dev
     kw = dict(CASES[name]); cid = kw.pop("cid")
     w = W.WORKLOADS[cid].scaled(**kw)
     n_cap = (w.n_ctx + 1 + 63) // 64 * 64
     x = W.make_inputs(w, n_cap=n_cap)
-    print("offload", name, flush=True)
-    d = Device(w, x)
+    if pairing == "interleaved":
+        x = W.as_interleaved(x)         # the same vectors, FC i stored at dims (2i, 2i+1)
+    print("offload", name, pairing, flush=True)
+    d = Device(w, x, pairing=pairing)
     nd = w.head_dim - 2 * w.n_fc
     Knd = _pinned((w.batch, w.n_kv_heads, n_cap, max(nd, 1)), d.st)
     Vh = _pinned(x["V"].shape, d.st)
@@ -52,7 +55,7 @@ def test_offload_step_matches_oracle_and_on_device_variant(fb, name):
     # Split: dominant pairs to the device copy, the rest to host memory
     fb.fasa_offload_split_kcache(d.shape, d.K, d.fc_idx, d.Kp, Knd, 0, w.n_ctx)
     torch.cuda.synchronize()
-    Kp_ref, Knd_ref = O.split_kcache(x["K"], x["fc_idx"], w.n_ctx)
+    Kp_ref, Knd_ref = O.split_kcache(x["K"], x["fc_idx"], w.n_ctx, pairing)
     np.testing.assert_array_equal(to_host(d.Kp, d.st)[:, :, :, :w.n_ctx], Kp_ref)
     knd_host = Knd.numpy().view(d.st) if d.st == np.uint16 else Knd.numpy()
     if nd > 0:
@@ -64,7 +67,7 @@ def test_offload_step_matches_oracle_and_on_device_variant(fb, name):
     torch.cuda.synchronize()
     bsel = d.bsel
     T = to_host(d.T)
-    S_ref, D_ref = O.score(x["q"], x["K"], x["fc_idx"], w.n_ctx)
+    S_ref, D_ref = O.score(x["q"], x["K"], x["fc_idx"], w.n_ctx, pairing)
     S = to_host(d.S)[:, :, :w.n_ctx].astype(np.float64)
     assert np.all(np.abs(S - S_ref) <= SCORE_RTOL * np.maximum(np.abs(S_ref), D_ref))
     np.testing.assert_array_equal(np.sort(T, -1), O.topk(to_host(d.S)[:, :, :w.n_ctx], w.budget, w.n_ctx))
@@ -75,7 +78,7 @@ def test_offload_step_matches_oracle_and_on_device_variant(fb, name):
     half = rows * bsel * w.head_dim * e
     KT = st_host[:half].view(d.st).reshape(w.batch, w.n_kv_heads, bsel, w.head_dim)
     VT = st_host[half:2 * half].view(d.st).reshape(w.batch, w.n_kv_heads, bsel, w.head_dim)
-    K_T_ref = O.combine_selected(Kp_ref, Knd_ref, x["fc_idx"], T)
+    K_T_ref = O.combine_selected(Kp_ref, Knd_ref, x["fc_idx"], T, pairing)
     for b in range(w.batch):
         for h in range(w.n_kv_heads):
             np.testing.assert_array_equal(KT[b, h], K_T_ref[b][h])

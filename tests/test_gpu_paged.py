@@ -55,7 +55,7 @@ def gather_from_pool(pool, table, page, layout):
 
 
 class PagedDevice:
-    def __init__(self, fb, w, x, page, layout, seed=7):
+    def __init__(self, fb, w, x, page, layout, seed=7, pairing="half"):
         from tests.gpu_util import to_dev
         self.w, self.page, self.layout = w, page, layout
         self.n_cap = x["n_cap"]
@@ -66,7 +66,8 @@ class PagedDevice:
         tdt = torch.int16 if w.dtype == "bf16" else torch.float32
         self.st = np.uint16 if w.dtype == "bf16" else np.float32
         self.shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_fc, w.n_ctx, self.n_cap,
-                                   w.budget, w.dtype, kv_stride_b=st["sb"], kv_stride_h=st["sh"], kv_stride_n=st["sn"])
+                                   w.budget, w.dtype, kv_stride_b=st["sb"], kv_stride_h=st["sh"], kv_stride_n=st["sn"],
+                                   pairing=pairing)
         self.paging = fb.make_paging(self.table, page, pk.shape[0])
         self.Kp = torch.zeros((w.batch, w.n_kv_heads, w.n_fc, self.n_cap, 2), dtype=tdt, device="cuda")
         self.S = torch.full((w.batch, w.n_kv_heads, self.n_cap), float("nan"), dtype=torch.float32, device="cuda")
