@@ -223,3 +223,31 @@ def test_calibration_and_offload_sizes_and_errors():
     assert L.fasa_offload_decode_step(C.byref(s), A, A, A, A, A, None, None, A, A, A, A, 1 << 40, A, 16, None) == fb.FASA_EWORKSPACE
     assert L.fasa_offload_decode_step(C.byref(s), A, A, A, None, A, None, None, A, A, A, A, 1 << 40, A, 1 << 40, None) == fb.FASA_EINVAL
     assert L.fasa_offload_split_kcache(C.byref(s), A, A, A, A, 5, 4, None) == fb.FASA_EINVAL
+
+
+def test_header_is_plain_c_and_structs_match_the_binding(tmp_path):
+    """include/fasa.h compiles as strict C99 and as C++, and the struct layouts the compiler sees are
+    the ones the ctypes binding marshals."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None or shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "layout.c"
+    fields_shape = [n for n, _ in fb.FasaShape._fields_]
+    fields_paging = [n for n, _ in fb.FasaPaging._fields_]
+    prints = ['printf("%zu\\n", sizeof(fasa_shape));', 'printf("%zu\\n", sizeof(fasa_paging));']
+    prints += ['printf("%%zu\\n", offsetof(fasa_shape, %s));' % f for f in fields_shape]
+    prints += ['printf("%%zu\\n", offsetof(fasa_paging, %s));' % f for f in fields_paging]
+    src.write_text('#include <stddef.h>\n#include <stdio.h>\n#include "fasa.h"\nint main(void) {\n%s\nreturn 0; }\n'
+                   % "\n".join(prints))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, str(src), "-o", str(exe)],
+                   check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c++",
+                    "-I", inc, str(src)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    want = [C.sizeof(fb.FasaShape), C.sizeof(fb.FasaPaging)]
+    want += [getattr(fb.FasaShape, f).offset for f in fields_shape]
+    want += [getattr(fb.FasaPaging, f).offset for f in fields_paging]
+    assert got == want
