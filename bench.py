@@ -43,6 +43,21 @@ MEASURED_TRAFFIC = {
     (1, "fasa_select"): 1393282 + 350168,
     (1, "fasa_sparse_attend"): 9206435 + 1089792,
     (1, "fasa_dense_attend"): 135503614 + 2162944,
+    # profiles/decode_step_batch16_n16384_b256_hbm_counters.txt
+    (2, "fasa_score_hist"): 134430506 + 9871694,
+    (2, "fasa_select"): 10815907 + 2746908,
+    (2, "fasa_sparse_attend"): 18315556 + 2412544,
+    (2, "fasa_dense_attend"): 1076186100 + 4558848,
+    # profiles/decode_step_longcot_batch8_gqa7_n32768_hbm_counters.txt
+    (3, "fasa_score_hist"): 67254132 + 4926245,
+    (3, "fasa_select"): 5267818 + 1915548,
+    (3, "fasa_sparse_attend"): 104514936 + 3879936,
+    (3, "fasa_dense_attend"): 539010014 + 3879936,
+    # profiles/decode_step_verylong_n131072_f32fc_b1024_hbm_counters.txt
+    (4, "fasa_score_hist"): 134342333 + 4947284,
+    (4, "fasa_select"): 4561410 + 340879,
+    (4, "fasa_sparse_attend"): 4713209 + 553216,
+    (4, "fasa_dense_attend"): 538111926 + 2162944,
 }
 
 
