@@ -408,6 +408,9 @@ def main():
     ap.add_argument("--recall-table", action="store_true",
                     help="selection quality only: recall of the full-head top-K set by F dominant FCs, for several "
                          "F and K (the synthetic analogue of the paper's compound contextual agreement table)")
+    ap.add_argument("--pairing", choices=["half", "interleaved", "list"], default="half",
+                    help="default mode only: how the dominant list names head dims (the same vectors re-stored "
+                         "with FC i at dims (2i, 2i+1), or the FCs written out as explicit dim pairs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only plain device copies of known size (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -453,6 +456,10 @@ def main():
     # ---------------- inputs: one seeded draw, cloned into R device-resident sets ----------------
     t0 = time.time()
     x = W.make_inputs(w)
+    if args.pairing == "interleaved":
+        x = W.as_interleaved(x)
+    elif args.pairing == "list":
+        x["fc_idx"] = W.explicit_pairs(x["fc_idx"], w.head_dim)
     log("inputs drawn in %.1fs" % (time.time() - t0))
     n_cap = x["n_cap"]
     tdt = torch.int16 if w.dtype == "bf16" else torch.float32
@@ -460,9 +467,10 @@ def main():
     R = args.sets or max(4, min(64, int(np.ceil(2.5 * LLC_BYTES / touched))))
     K_steps = max(R, (args.steps // R) * R) if not args.no_graph else args.steps
     dev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
-    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_fc, w.n_ctx, n_cap, w.budget, w.dtype)
+    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_fc, w.n_ctx, n_cap, w.budget, w.dtype,
+                          pairing=args.pairing)
     ws_bytes = fb.fasa_workspace_bytes(shape)
-    q0, K0, V0, fc = dev(x["q"]), dev(x["K"]), dev(x["V"]), dev(x["fc_idx"])
+    q0, K0, V0, fc = dev(x["q"]), dev(x["K"]), dev(x["V"]), dev(np.ascontiguousarray(x["fc_idx"]))
     sets = []
     for r in range(R):
         s = {
@@ -613,8 +621,12 @@ def main():
     if w.n_fc < w.head_dim // 2 and bsel < w.n_ctx:
         half = w.head_dim // 2
         s0 = sets[0]
-        fc_all = torch.arange(half, dtype=torch.int32, device="cuda").repeat(w.n_kv_heads, 1).contiguous()
-        shape_all = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, half, w.n_ctx, n_cap, w.budget, w.dtype)
+        fc_all_host = np.tile(np.arange(half, dtype=np.int32), (w.n_kv_heads, 1))
+        if args.pairing == "list":
+            fc_all_host = W.explicit_pairs(fc_all_host, w.head_dim)
+        fc_all = dev(np.ascontiguousarray(fc_all_host))
+        shape_all = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, half, w.n_ctx, n_cap, w.budget, w.dtype,
+                                  pairing=args.pairing)
         Kp_all = torch.zeros((w.batch, w.n_kv_heads, half, n_cap, 2), dtype=tdt, device="cuda")
         S_all = torch.zeros_like(s0["S"]); T_all = torch.zeros_like(s0["T"])
         fb.fasa_pack_kcache(shape_all, s0["K"], fc_all, Kp_all, 0, w.n_ctx)
@@ -635,7 +647,7 @@ def main():
         qs, Ks, Vs = x["q"][sub], x["K"][sub], x["V"][sub]
         reps, t_cpu0, c0 = 0, time.time(), time.process_time()
         while True:
-            O.decode_step(qs, Ks, Vs, x["fc_idx"], w.n_ctx, w.budget)
+            O.decode_step(qs, Ks, Vs, x["fc_idx"], w.n_ctx, w.budget, pairing=args.pairing)
             reps += 1
             if time.time() - t_cpu0 >= 10.0 or reps >= 200:
                 break
@@ -654,7 +666,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "n_ctx": w.n_ctx, "budget": bsel, "n_fc": w.n_fc,
-                   "storage_dtype": w.dtype, "buffer_sets": R, "launch": mode},
+                   "storage_dtype": w.dtype, "pairing": args.pairing, "buffer_sets": R, "launch": mode},
         "hbm": {"alg_bytes": model["alg"], "alg_plus_intermediate_bytes": model["alg_plus_intermediates"],
                 "step_gbps": round(model["alg"] / us_per_step / 1e3, 1),
                 "step_frac_of_peak": round(model["alg"] / us_per_step / 1e3 / HBM_PEAK_GBPS, 4),

@@ -307,8 +307,8 @@ static hipError_t launch_score_h(const fasa_shape& s, const void* q, void* Kp, c
   switch (s.pairing) {
     case FASA_PAIR_INTERLEAVED:
       return launch_score_f<ET, HIST, APPEND, FASA_PAIR_INTERLEAVED>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
-    case FASA_PAIR_LIST:   // explicit dim pairs: the any-F kernel only
-      return launch_score_v<ET, HIST, 0, APPEND, FASA_PAIR_LIST>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    case FASA_PAIR_LIST:
+      return launch_score_f<ET, HIST, APPEND, FASA_PAIR_LIST>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
     default:
       return launch_score_f<ET, HIST, APPEND, FASA_PAIR_ROTATE_HALF>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
   }
