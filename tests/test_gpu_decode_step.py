@@ -96,6 +96,9 @@ REDUCED = {
     "fc8_f32": dict(cid=0, n_ctx=1030, budget=100, n_fc=8),
     "fc40": dict(cid=1, n_ctx=3000, budget=200, n_fc=40),
     "fc64": dict(cid=1, n_ctx=2100, budget=200, n_fc=64),
+    # many short rows (768 workgroup rows), and a row count that is no multiple of the 8 dies
+    "many_rows": dict(cid=2, batch=96, n_ctx=700, budget=64),
+    "odd_rows": dict(cid=1, batch=11, n_kv_heads=3, n_q_heads=6, n_ctx=900, budget=50),
 }
 
 
