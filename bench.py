@@ -41,7 +41,7 @@ MEASURED_TRAFFIC = {
     # profiles/decode_step_llama3_8b_layer_n32768_b2048_hbm_counters.txt
     (1, "fasa_score_hist"): 16876270 + 1235328,
     (1, "fasa_select"): 1393282 + 350168,
-    (1, "fasa_sparse_attend"): 9206435 + 1089792,
+    (1, "fasa_sparse_attend"): 9188383 + 1089792,
     (1, "fasa_dense_attend"): 135503614 + 2162944,
     # profiles/decode_step_batch16_n16384_b256_hbm_counters.txt
     (2, "fasa_score_hist"): 134430506 + 9871694,

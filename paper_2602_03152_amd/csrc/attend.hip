@@ -37,24 +37,41 @@ template <> struct Row8<float> {
 __device__ __forceinline__ float to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 __device__ __forceinline__ float to_f32(float v) { return v; }
 
+// 16-byte load that is coherent at agent scope (served from the coherence point like an agent-scope
+// atomic load, which the language only offers up to 8 bytes).  The compiler does not count this load:
+// agent_b128_wait() must run before the destination is read.
+typedef float f32x4_ld __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void agent_b128_issue(f32x4_ld& dst, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
+}
+// waits for every outstanding vector memory operation of the wave; the eight destinations are tied
+// to the statement so that no use of them can be moved above it
+__device__ __forceinline__ void agent_b128_wait(f32x4_ld* x) {
+  asm volatile("s_waitcnt vmcnt(0)"
+               : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
+               :: "memory");
+}
+
 // Merges the split partials of one row into O.  Called by the row's last workgroup (all 256
 // threads).  The partials were published by other workgroups with agent-scope stores and are read
-// with agent-scope loads, 8 bytes (two head dims) at a time.  One memory round trip: every thread
-// first requests the (max, sum) pairs its wave turns into weights, then ALL the weighted-V partials
-// it will sum (they do not depend on the weights) - a split's partial is C = 64 G columns of two
-// floats; thread t owns column t (and t + 256 when C > 256), or, when C <= 128, column t mod C of
-// every P-th split, the P partitions meeting in LDS at the end.
+// with agent-scope loads, the weighted-V partials 16 bytes at a time: one CU's rate of load requests
+// bounds this phase, so the wider the request the better (64 KB of fresh partials: 0.8 us with
+// 16-byte loads against 1.4 us with 8-byte ones; an acquire fence followed by ordinary loads reads as
+// fast but slows the other workgroups of the die down).  One memory round trip: every
+// thread first requests the (max, sum) pairs its wave turns into weights, then ALL the weighted-V
+// partials it will sum (they do not depend on the weights) - a split's partial is C = 32 G columns of
+// four floats; thread t owns column t mod C of every P-th split, the P partitions meeting in LDS at
+// the end.
 template <int G>
 __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
                                             const float* __restrict__ part_ml,
                                             float* __restrict__ O, int row, int b, int h, int Hq,
                                             int n_splits, float* wsm /* [G][kMaxSplitsLds] */,
-                                            float* red /* [G] */, float* xbuf /* [3][C][2] */) {
+                                            float* red /* [G] */, float* xbuf /* [P - 1][C][4] */) {
   constexpr int D = kHeadDim;
-  constexpr int C = G * (D / 2);
-  constexpr int CPT = (C + 255) / 256;
-  constexpr int P = CPT > 1 ? 1 : (256 / C >= 4 ? 4 : (256 / C >= 2 ? 2 : 1));
-  constexpr int RS = 64 / CPT;          // splits in flight per thread and round
+  constexpr int C = G * (D / 4);
+  constexpr int P = 256 / C >= 4 ? 4 : (256 / C >= 2 ? 2 : 1);
+  constexpr int RS = 32;                // splits in flight per thread and round
   constexpr int NG = (G + 3) / 4;
   const int t = threadIdx.x;
   const int wave = t >> 6, lane = t & 63;
@@ -62,7 +79,6 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
 #ifdef FASA_TRACE
   unsigned long long ct[4]; ct[0] = wall_clock64();
 #endif
-
   // (max, sum) pairs: wave w serves query heads w, w + 4; lane = split (+ 64 i).  Indices are
   // clamped, not tested: the duplicates are masked below.
   float2 ml[NG][kMaxSplitsLds / 64];
@@ -76,12 +92,12 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
     }
   }
 
-  const int part = CPT > 1 ? 0 : t / C;                 // split partition of this thread
-  const int c0 = CPT > 1 ? t : t % C;
-  const bool owner = CPT > 1 || t < P * C;
-  const float2* pa = reinterpret_cast<const float2*>(part_acc + rbase * D);
+  const int part = t / C;                               // split partition of this thread
+  const int c0 = t % C;
+  const bool owner = t < P * C;
+  const float4* pa = reinterpret_cast<const float4*>(part_acc + rbase * D);
   const int K = (n_splits + P - 1) / P;                 // splits per partition
-  float2 x[RS][CPT];
+  f32x4_ld x[RS];
   auto load_round = [&](int k0) {
 #pragma unroll
     for (int u0 = 0; u0 < RS; u0 += 8) {
@@ -89,9 +105,7 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
 #pragma unroll
         for (int u = u0; u < u0 + 8; ++u) {
           const int sp = min(part + P * (k0 + u), n_splits - 1);
-#pragma unroll
-          for (int j = 0; j < CPT; ++j)
-            x[u][j] = ld_agent(pa + (size_t)sp * C + min(c0 + 256 * j, C - 1));
+          agent_b128_issue(x[u], pa + (size_t)sp * C + c0);
         }
       }
     }
@@ -122,34 +136,30 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
   ct[1] = wall_clock64();
 #endif
 
-  float2 a[CPT];
-#pragma unroll
-  for (int j = 0; j < CPT; ++j) a[j] = make_float2(0.f, 0.f);
+  const int gcol = min(c0 / (D / 4), G - 1);            // query head of this thread's column
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int k0 = 0; k0 < K; k0 += RS) {
     if (k0) load_round(k0);
 #pragma unroll
     for (int u0 = 0; u0 < RS; u0 += 8) {
       if (k0 + u0 < K) {
+        agent_b128_wait(&x[u0]);
         // straight-line inside a chunk of 8 splits: the weight reads go out together.  A split
         // beyond the row's count has a finite (re-read) partial and weight 0.
-        float wgt[8][CPT];
+        float wgt[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
           const int sp = part + P * (k0 + u0 + u);
-#pragma unroll
-          for (int j = 0; j < CPT; ++j) {
-            const int c = min(c0 + 256 * j, C - 1);
-            const float w0 = wsm[(c / (D / 2)) * kMaxSplitsLds + min(sp, kMaxSplitsLds - 1)];
-            wgt[u][j] = sp < n_splits ? w0 : 0.f;
-          }
+          const float w0 = wsm[gcol * kMaxSplitsLds + min(sp, kMaxSplitsLds - 1)];
+          wgt[u] = sp < n_splits ? w0 : 0.f;
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-#pragma unroll
-          for (int j = 0; j < CPT; ++j) {
-            a[j].x = fmaf(x[u0 + u][j].x, wgt[u][j], a[j].x);
-            a[j].y = fmaf(x[u0 + u][j].y, wgt[u][j], a[j].y);
-          }
+        for (int u = 0; u < 8; ++u) {
+          a.x = fmaf(x[u0 + u].x, wgt[u], a.x);
+          a.y = fmaf(x[u0 + u].y, wgt[u], a.y);
+          a.z = fmaf(x[u0 + u].z, wgt[u], a.z);
+          a.w = fmaf(x[u0 + u].w, wgt[u], a.w);
+        }
       }
     }
   }
@@ -158,29 +168,22 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
   if (t == 0 && row == 0) printf("combine: weights %llu acc %llu (x10ns) n_splits %d\n", ct[1]-ct[0], ct[2]-ct[1], n_splits);
 #endif
   if constexpr (P > 1) {
-    float2* xb = reinterpret_cast<float2*>(xbuf);
-    if (owner && part > 0) xb[(part - 1) * C + c0] = a[0];
+    float4* xb = reinterpret_cast<float4*>(xbuf);
+    if (owner && part > 0) xb[(part - 1) * C + c0] = a;
     __syncthreads();
     if (owner && part == 0) {
 #pragma unroll
       for (int pp = 1; pp < P; ++pp) {
-        const float2 o = xb[(pp - 1) * C + c0];
-        a[0].x += o.x;
-        a[0].y += o.y;
+        const float4 o = xb[(pp - 1) * C + c0];
+        a.x += o.x; a.y += o.y; a.z += o.z; a.w += o.w;
       }
     }
   }
   if (owner && part == 0) {
-#pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-      const int c = c0 + 256 * j;
-      if (c < C) {
-        const int g = c / (D / 2), d2 = c % (D / 2);
-        const float r = red[g];
-        *reinterpret_cast<float2*>(O + ((size_t)b * Hq + (size_t)h * G + g) * D + 2 * d2) =
-            make_float2(a[j].x * r, a[j].y * r);
-      }
-    }
+    const int g = c0 / (D / 4), d4 = c0 % (D / 4);
+    const float r = red[g];
+    *reinterpret_cast<float4*>(O + ((size_t)b * Hq + (size_t)h * G + g) * D + 4 * d4) =
+        make_float4(a.x * r, a.y * r, a.z * r, a.w * r);
   }
 }
 
