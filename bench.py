@@ -336,6 +336,101 @@ def ragged(args, w, fb, W, np, torch):
     print(json.dumps(out), flush=True)
 
 
+def paged(args, w, fb, W, np, torch):
+    """The decode step on a paged K/V cache (blocks of --paged tokens at random places of a pool, token-major
+    blocks), timed next to the same step on the contiguous cache, both over rotating buffer sets."""
+    page = args.paged
+    x = W.make_inputs(w)
+    n_cap = x["n_cap"]
+    assert page >= 1 and page & (page - 1) == 0 and n_cap % page == 0, "--paged takes a power of two dividing the capacity"
+    B, Hkv, D = w.batch, w.n_kv_heads, w.head_dim
+    nblk = n_cap // page
+    n_pool = B * nblk + 3                                   # three blocks that belong to nobody
+    rng = np.random.default_rng(20260203)
+    table = rng.permutation(n_pool)[: B * nblk].reshape(B, nblk).astype(np.int32)
+
+    def to_pool(a):                                         # [B][Hkv][n_cap][D] -> [block][token][head][dim]
+        pool = np.zeros((n_pool, page, Hkv, D), dtype=a.dtype)
+        blocks = a.reshape(B, Hkv, nblk, page, D).transpose(0, 2, 3, 1, 4)     # [B][nblk][page][Hkv][D]
+        pool[table.reshape(-1)] = blocks.reshape(B * nblk, page, Hkv, D)
+        return pool
+
+    dev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+    tdt = torch.int16 if w.dtype == "bf16" else torch.float32
+    bsel = min(w.budget, w.n_ctx)
+    shape_c = fb.make_shape(B, w.n_q_heads, Hkv, D, w.n_fc, w.n_ctx, n_cap, w.budget, w.dtype)
+    shape_p = fb.make_shape(B, w.n_q_heads, Hkv, D, w.n_fc, w.n_ctx, n_cap, w.budget, w.dtype,
+                            kv_stride_b=page * Hkv * D, kv_stride_h=D, kv_stride_n=Hkv * D)
+    ws_bytes = fb.fasa_workspace_bytes(shape_p)
+    table_dev = torch.from_numpy(table).cuda()
+    paging = fb.make_paging(table_dev, page, n_pool)
+    q0, fc = dev(x["q"]), dev(x["fc_idx"])
+    Kc0, Vc0, Kp0, Vp0 = dev(x["K"]), dev(x["V"]), dev(to_pool(x["K"])), dev(to_pool(x["V"]))
+    touched = W.algorithmic_bytes(w)["alg_plus_intermediates"]
+    R = args.sets or max(4, min(32, int(np.ceil(2.5 * LLC_BYTES / touched))))
+    sets = []
+    for r in range(R):
+        s = {"q": q0.clone(), "Kc": Kc0.clone(), "Vc": Vc0.clone(), "Kpool": Kp0.clone(), "Vpool": Vp0.clone()}
+        for tag in ("c", "p"):
+            s["Kp" + tag] = torch.zeros((B, Hkv, w.n_fc, n_cap, 2), dtype=tdt, device="cuda")
+            s["S" + tag] = torch.zeros((B, Hkv, n_cap), dtype=torch.float32, device="cuda")
+            s["T" + tag] = torch.zeros((B, Hkv, bsel), dtype=torch.int32, device="cuda")
+            s["O" + tag] = torch.zeros((B, w.n_q_heads, D), dtype=torch.float32, device="cuda")
+            s["ws" + tag] = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+            fb.fasa_workspace_init(shape_p, s["ws" + tag], ws_bytes)
+        fb.fasa_pack_kcache(shape_c, s["Kc"], fc, s["Kpc"], 0, w.n_ctx)
+        fb.fasa_pack_kcache_paged(shape_p, paging, s["Kpool"], fc, s["Kpp"], 0, w.n_ctx)
+        sets.append(s)
+    torch.cuda.synchronize()
+
+    def step_c(s):
+        fb.fasa_decode_step(shape_c, s["q"], s["Kc"], s["Vc"], s["Kpc"], fc, None, None, s["Sc"], s["Tc"], s["Oc"],
+                            s["wsc"], ws_bytes)
+
+    def step_p(s):
+        fb.fasa_decode_step_paged(shape_p, paging, s["q"], s["Kpool"], s["Vpool"], s["Kpp"], fc, None, None, None, None,
+                                  s["Sp"], s["Tp"], s["Op"], s["wsp"], ws_bytes)
+
+    K_steps = max(R, (args.steps // R) * R)
+    res = {}
+    for name, fn in (("contiguous", step_c), ("paged", step_p)):
+        for i in range(args.warmup):
+            fn(sets[i % R])
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(K_steps):
+            fn(sets[i % R])
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) / K_steps * 1e3
+        fb.fasa_profile_reset(); fb.fasa_profile_enable(True)
+        for i in range(K_steps):
+            fn(sets[i % R])
+        prof = fb.profile_summary()
+        fb.fasa_profile_enable(False); fb.fasa_profile_reset()
+        res[name] = {"us_per_step": round(us, 3),
+                     "kernels": {k: round(ms / n * 1e3, 3) for k, (n, ms) in prof.items()}}
+        log("%s: %.2f us/step %s" % (name, us, res[name]["kernels"]))
+    s0 = sets[0]
+    same_set = bool(np.array_equal(np.sort(s0["Tc"].cpu().numpy(), -1), np.sort(s0["Tp"].cpu().numpy(), -1)))
+    o_diff = float((s0["Oc"] - s0["Op"]).abs().max())
+    assert same_set and o_diff <= 2e-5, (same_set, o_diff)
+    us = res["paged"]["us_per_step"]
+    out = {
+        "metric": "us_per_decode_step", "value": us, "unit": "us", "n_gpus": 1, "steps": K_steps,
+        "warmup": args.warmup, "ms_per_step": round(us / 1e3, 6), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name + "_paged", "batch": B, "n_q_heads": w.n_q_heads, "n_kv_heads": Hkv,
+                   "head_dim": D, "n_ctx": w.n_ctx, "budget": bsel, "n_fc": w.n_fc, "storage_dtype": w.dtype,
+                   "page_size": page, "pool_blocks": n_pool, "block_layout": "[block][token][head][dim]",
+                   "buffer_sets": R, "launch": "eager"},
+        "paged": res["paged"], "contiguous": res["contiguous"],
+        "same_index_set_as_contiguous": same_set, "max_abs_output_difference": o_diff,
+    }
+    print(json.dumps(out), flush=True)
+
+
 def recall_table(args, w, fb, W, np, torch):
     """Selection quality on the synthetic workload, in the form of the paper's compound contextual
     agreement table (Sec. 3.3): for F dominant FCs and a top-K, the share of the full-head top-K set
@@ -405,6 +500,9 @@ def main():
     ap.add_argument("--ragged", type=int, default=0, metavar="STEPS",
                     help="serving loop: mixed sequence lengths growing by one per step, one captured graph "
                          "with the lengths on the device; use with --config 2")
+    ap.add_argument("--paged", type=int, default=0, metavar="PAGE",
+                    help="time the step on a paged K/V cache (blocks of PAGE tokens scattered over a pool) next to "
+                         "the contiguous cache")
     ap.add_argument("--recall-table", action="store_true",
                     help="selection quality only: recall of the full-head top-K set by F dominant FCs, for several "
                          "F and K (the synthetic analogue of the paper's compound contextual agreement table)")
@@ -447,6 +545,8 @@ def main():
         return calibrate(args, w, fb, W, np, torch)
     if args.ragged:
         return ragged(args, w, fb, W, np, torch)
+    if args.paged:
+        return paged(args, w, fb, W, np, torch)
     if args.recall_table:
         return recall_table(args, w, fb, W, np, torch)
     rows = w.batch * w.n_kv_heads
