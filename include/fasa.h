@@ -150,6 +150,24 @@ int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, v
                      const int32_t* fc_idx, const void* k_new, const void* v_new, float* S,
                      int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream);
 
+/* fasa_decode_step for callers that cannot allocate device memory or hand over a workspace: code
+ * running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * workspace is an array inside the library, FASA_STATIC_WS_BYTES per GPU, held by every GPU the
+ * library is loaded on until the process ends.  The call allocates and frees nothing; it launches one
+ * small clearing kernel (no memset node) and then the kernels of fasa_decode_step.
+ *   - Shapes whose workspace (fasa_workspace_bytes without the paged-cache slot list) exceeds
+ *     FASA_STATIC_WS_BYTES are refused with FASA_EWORKSPACE before any HIP call.
+ *   - No fasa_workspace_init is needed: every call clears what must start at zero.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race.  Order them on one stream.
+ *   - The first call on a device looks the array's address up (hipGetSymbolAddress) and must not be
+ *     made while the stream is being captured; later calls may be.
+ * Arguments and results otherwise as fasa_decode_step. */
+#define FASA_STATIC_WS_BYTES (32u << 20)
+int fasa_decode_step_static(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,
+                            const int32_t* fc_idx, const void* k_new, const void* v_new, float* S,
+                            int32_t* T, float* O, void* stream);
+
 /* fasa_decode_step for a batch whose sequences differ in length (paper Sec. 4.1-4.2 per sequence;
  * the decode loop of Alg. 2 where t advances every step): the lengths live on the DEVICE, so the
  * same call - or one captured HIP graph of it - serves every step of a growing, ragged batch.

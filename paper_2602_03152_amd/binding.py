@@ -23,7 +23,7 @@ FASA_PAIR_ROTATE_HALF, FASA_PAIR_INTERLEAVED, FASA_PAIR_LIST = 0, 1, 2
 
 EXPORTS = [
     "fasa_workspace_bytes", "fasa_workspace_init", "fasa_validate_fc_idx", "fasa_pack_kcache", "fasa_score", "fasa_topk",
-    "fasa_sparse_attend", "fasa_dense_attend", "fasa_decode_step", "fasa_decode_step_ragged",
+    "fasa_sparse_attend", "fasa_dense_attend", "fasa_decode_step", "fasa_decode_step_static", "fasa_decode_step_ragged",
     "fasa_pack_kcache_paged", "fasa_decode_step_paged",
     "fasa_offload_stage_bytes",
     "fasa_offload_split_kcache", "fasa_offload_decode_step", "fasa_calibration_workspace_bytes",
@@ -73,6 +73,8 @@ def _load():
     lib.fasa_dense_attend.argtypes = [SP, P, P, P, P, P, SZ, P]; lib.fasa_dense_attend.restype = C.c_int
     lib.fasa_decode_step.argtypes = [SP, P, P, P, P, P, P, P, P, P, P, P, SZ, P]
     lib.fasa_decode_step.restype = C.c_int
+    lib.fasa_decode_step_static.argtypes = [SP, P, P, P, P, P, P, P, P, P, P, P]
+    lib.fasa_decode_step_static.restype = C.c_int
     lib.fasa_decode_step_ragged.argtypes = [SP, P, P, P, P, P, P, P, P, P, P, P, P, P, SZ, P]
     lib.fasa_decode_step_ragged.restype = C.c_int
     PP = C.POINTER(FasaPaging)
@@ -182,6 +184,15 @@ def fasa_decode_step(shape, q, K, V, Kp, fc_idx, k_new, v_new, S, T, O, ws, ws_b
     _check(_lib.fasa_decode_step(C.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(Kp), _ptr(fc_idx),
                                  _ptr(k_new), _ptr(v_new), _ptr(S), _ptr(T), _ptr(O), _ptr(ws), ws_bytes,
                                  _stream(stream)), "fasa_decode_step")
+
+
+FASA_STATIC_WS_BYTES = 32 << 20
+
+
+def fasa_decode_step_static(shape, q, K, V, Kp, fc_idx, k_new, v_new, S, T, O, stream=None) -> None:
+    _check(_lib.fasa_decode_step_static(C.byref(shape), _ptr(q), _ptr(K), _ptr(V), _ptr(Kp), _ptr(fc_idx),
+                                        _ptr(k_new), _ptr(v_new), _ptr(S), _ptr(T), _ptr(O), _stream(stream)),
+           "fasa_decode_step_static")
 
 
 def fasa_decode_step_ragged(shape, q, K, V, Kp, fc_idx, k_new, v_new, n_ctx_seq, budget_seq, S, T, O, ws,

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -159,6 +160,39 @@ static int check_paging(const fasa_paging* p, const fasa_shape* s, PageMap* out)
 }
 
 #define FASA_HIP(expr) do { if ((expr) != hipSuccess) return FASA_EHIP; } while (0)
+
+// ---------------------------------------------------------------------------------------------
+// The library's own workspace for fasa_decode_step_static: one array per GPU, part of the code
+// object, held by every device the library is loaded on until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels and clears get the address that
+// call returns, looked up once per device.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[FASA_STATIC_WS_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// device address of `scratch` on the current device (nullptr: a HIP call failed, see last error)
+static void* scratch_of_current_device() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    set_last_hip_error(e != hipSuccess ? e : hipErrorInvalidDevice);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) {
+      set_last_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol);
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
 
 }  // namespace fasa
 
@@ -320,6 +354,25 @@ int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, v
                      int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream) {
   return decode_step_common(shape, nullptr, q, K, V, Kp, fc_idx, k_new, v_new, nullptr, nullptr, S, T, O, ws,
                             ws_bytes, stream);
+}
+
+int fasa_decode_step_static(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,
+                            const int32_t* fc_idx, const void* k_new, const void* v_new, float* S,
+                            int32_t* T, float* O, void* stream) {
+  // everything that can be refused is refused before the first HIP call
+  int rc = check_shape(shape, kNeedCtx | kNeedBudget | kNeedFc | kNeedStrides);
+  if (rc != FASA_OK) return rc;
+  const WsLayout w = ws_layout(*shape);
+  if (w.tslot_off > (size_t)FASA_STATIC_WS_BYTES) return FASA_EWORKSPACE;
+  if (!q || !K || !V || !Kp || !fc_idx || !S || !T || !O) return FASA_EINVAL;
+  void* ws = scratch_of_current_device();
+  if (!ws) return FASA_EHIP;
+  // The array keeps what the last call left, and that call may have had another layout: the part
+  // that has to start at zero is cleared by a kernel (a caller may be capturing this stream).
+  FASA_HIP(launch_ws_clear(*shape, (uint32_t*)((char*)ws + w.hist_off), (RowCtl*)((char*)ws + w.ctl_off),
+                           (hipStream_t)stream));
+  return decode_step_common(shape, nullptr, q, K, V, Kp, fc_idx, k_new, v_new, nullptr, nullptr, S, T, O, ws,
+                            w.tslot_off, stream);
 }
 
 int fasa_decode_step_ragged(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,

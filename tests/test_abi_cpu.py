@@ -185,6 +185,21 @@ def test_workspace_too_small():
     assert L.fasa_decode_step(C.byref(s), A, A, A, A, A, None, None, A, A, A, A, 0, None) == fb.FASA_EWORKSPACE
 
 
+def test_static_workspace_entry_point_refuses_before_any_hip_call():
+    """fasa_decode_step_static: bad shapes, null pointers and shapes whose workspace exceeds the
+    library's own array are refused on a host without a GPU (no HIP call is made before that)."""
+    L = fb.lib
+    assert fb.FASA_STATIC_WS_BYTES == 32 << 20
+    text = open(os.path.join(ROOT, "include", "fasa.h")).read()
+    assert re.search(r"#define\s+FASA_STATIC_WS_BYTES\s+\(32u\s*<<\s*20\)", text)
+    big = _shape(batch=64, n_ctx=65536, n_cap=65536, budget=4096)
+    assert fb.fasa_workspace_bytes(big) > fb.FASA_STATIC_WS_BYTES
+    assert L.fasa_decode_step_static(C.byref(big), A, A, A, A, A, None, None, A, A, A, None) == fb.FASA_EWORKSPACE
+    assert L.fasa_decode_step_static(C.byref(_shape(budget=0)), A, A, A, A, A, None, None, A, A, A, None) == fb.FASA_EINVAL
+    assert L.fasa_decode_step_static(C.byref(_shape()), None, A, A, A, A, None, None, A, A, A, None) == fb.FASA_EINVAL
+    assert L.fasa_decode_step_static(None, A, A, A, A, A, None, None, A, A, A, None) == fb.FASA_EINVAL
+
+
 def test_binding_raises():
     s = _shape(budget=0)
     with pytest.raises(fb.FasaError) as e:
