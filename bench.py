@@ -509,6 +509,9 @@ def main():
     ap.add_argument("--pairing", choices=["half", "interleaved", "list"], default="half",
                     help="default mode only: how the dominant list names head dims (the same vectors re-stored "
                          "with FC i at dims (2i, 2i+1), or the FCs written out as explicit dim pairs)")
+    ap.add_argument("--stage-timers", action="store_true",
+                    help="with FASA_LIB pointing at the traced library (python -m paper_2602_03152_amd.build --trace): "
+                         "run three steps and let the kernels print their phase times for row 0; nothing is timed")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only plain device copies of known size (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -594,6 +597,13 @@ def main():
 
     def dense(s):
         fb.fasa_dense_attend(shape, s["q"], s["K"], s["V"], s["O"], s["ws"], ws_bytes)
+
+    if args.stage_timers:
+        for i in range(3):
+            step(sets[0])
+            torch.cuda.synchronize()
+            print("---- step %d ----" % i, flush=True)
+        return
 
     def time_loop(fn, n_steps, warm):
         for i in range(warm):

@@ -15,7 +15,8 @@ from typing import Optional
 # soname and must bind to the copy torch's allocator and streams live in, not to a second one.
 import torch  # noqa: F401
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfasa.so")
+# FASA_LIB names another build of the same library (the traced one of build.py --trace); default: in-tree
+_LIB_PATH = os.environ.get("FASA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfasa.so")
 
 FASA_OK, FASA_EINVAL, FASA_EUNSUPPORTED, FASA_EWORKSPACE, FASA_EHIP = 0, -1, -2, -3, -4
 FASA_BF16, FASA_F32 = 0, 1

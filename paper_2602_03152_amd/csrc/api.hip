@@ -96,12 +96,15 @@ WsLayout ws_layout(const fasa_shape& s) {
   const int sp_sparse = plan_attend(w.rows, bsel, G).n_splits;
   const int sp_dense = plan_attend(w.rows, s.n_ctx, G).n_splits;
   w.max_splits = sp_sparse > sp_dense ? sp_sparse : sp_dense;
+  const int sp_fused = plan_fused(s, true).nslices;      // the fused step: one partial per score slice
+  if (sp_fused > w.max_splits) w.max_splits = sp_fused;
   size_t off = 0;
   w.hist_off = off;      off = align256(off + (size_t)w.rows * kHistBins * sizeof(uint32_t));
   w.ctl_off = off;       off = align256(off + (size_t)w.rows * sizeof(RowCtl));
   w.cand_off = off;      off = align256(off + (size_t)w.rows * s.n_cap * sizeof(uint2));
   w.part_acc_off = off;  off = align256(off + (size_t)w.rows * w.max_splits * G * kHeadDim * sizeof(float));
   w.part_ml_off = off;   off = align256(off + (size_t)w.rows * w.max_splits * G * 2 * sizeof(float));
+  w.rec_off = off;       off = align256(off + (size_t)w.rows * kFuseRecBytesPerRow);   // candidate records (fused step)
   // pool slots of the selected tokens (paged caches); at the end: earlier offsets do not depend on it
   w.tslot_off = off;     off = align256(off + (size_t)w.rows * (size_t)bsel * sizeof(int32_t));
   w.total = off;
@@ -341,6 +344,14 @@ static int decode_step_common(const fasa_shape* shape, const fasa_paging* paging
   const bool select_all = !by_sequence && shape->budget >= shape->n_ctx;
   // the new row (if any) joins K, V and Kp inside the scoring kernel
   const AppendArgs ap{k_new, v_new, K, V, pm};
+  const FusePlan fp = plan_fused(*shape, by_sequence);
+  if (fp.tpb != 0) {
+    // two launches: scores + adaptive histogram, then selection and attention by token-range ownership
+    FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, hist, st, rl, ap, ctl));
+    FASA_HIP(launch_select_attend(*shape, fp, q, K, V, S, hist, ctl, cand, T, O, (float*)(base + w.part_acc_off),
+                                  (float*)(base + w.part_ml_off), (unsigned char*)(base + w.rec_off), st, rl, pm));
+    return FASA_OK;
+  }
   FASA_HIP(launch_score(*shape, q, Kp, fc_idx, S, select_all ? nullptr : hist, st, rl, ap));
   FASA_HIP(launch_select(*shape, S, hist, ctl, cand, T, st, rl, pm, Tslot));
   // paged cache: the attention kernel gathers by pool slot and does not read the table again

@@ -3,15 +3,12 @@
 // K/V rows it names, keeps a running (max, sum, weighted V) per query head of the GQA group, and
 // the workgroup that finishes a row last merges the row's chunks.  The same kernel with the index list replaced by the
 // identity is the full-KV baseline (paper Sec. 4.4).
-#include "fasa_device.h"
-#include "fasa_internal.h"
+#include "attend_common.h"
 
 namespace fasa {
 
 constexpr int kAttU = 4;                  // rows in flight per 16-lane group and batch
 constexpr int kAttBatch = 4 * kAttU;      // rows per wave and batch
-constexpr float kNegBig = -1.0e30f;       // finite stand-in for -inf (keeps exp2 arguments finite)
-constexpr int kMaxSplitsLds = 256;        // most splits per row the merging workgroup can weight
 
 // 8 consecutive head dims of one cached row, widened to float32
 template <typename ET> struct Row8;
@@ -36,156 +33,6 @@ template <> struct Row8<float> {
 
 __device__ __forceinline__ float to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 __device__ __forceinline__ float to_f32(float v) { return v; }
-
-// 16-byte load that is coherent at agent scope (served from the coherence point like an agent-scope
-// atomic load, which the language only offers up to 8 bytes).  The compiler does not count this load:
-// agent_b128_wait() must run before the destination is read.
-typedef float f32x4_ld __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void agent_b128_issue(f32x4_ld& dst, const void* p) {
-  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
-}
-// waits for every outstanding vector memory operation of the wave; the eight destinations are tied
-// to the statement so that no use of them can be moved above it
-__device__ __forceinline__ void agent_b128_wait(f32x4_ld* x) {
-  asm volatile("s_waitcnt vmcnt(0)"
-               : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
-               :: "memory");
-}
-
-// Merges the split partials of one row into O.  Called by the row's last workgroup (all 256
-// threads).  The partials were published by other workgroups with agent-scope stores and are read
-// with agent-scope loads, the weighted-V partials 16 bytes at a time: one CU's rate of load requests
-// bounds this phase, so the wider the request the better (64 KB of fresh partials: 0.8 us with
-// 16-byte loads against 1.4 us with 8-byte ones; an acquire fence followed by ordinary loads reads as
-// fast but slows the other workgroups of the die down).  One memory round trip: every
-// thread first requests the (max, sum) pairs its wave turns into weights, then ALL the weighted-V
-// partials it will sum (they do not depend on the weights) - a split's partial is C = 32 G columns of
-// four floats; thread t owns column t mod C of every P-th split, the P partitions meeting in LDS at
-// the end.
-template <int G>
-__device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
-                                            const float* __restrict__ part_ml,
-                                            float* __restrict__ O, int row, int b, int h, int Hq,
-                                            int n_splits, float* wsm /* [G][kMaxSplitsLds] */,
-                                            float* red /* [G] */, float* xbuf /* [P - 1][C][4] */) {
-  constexpr int D = kHeadDim;
-  constexpr int C = G * (D / 4);
-  constexpr int P = 256 / C >= 4 ? 4 : (256 / C >= 2 ? 2 : 1);
-  constexpr int RS = 32;                // splits in flight per thread and round
-  constexpr int NG = (G + 3) / 4;
-  const int t = threadIdx.x;
-  const int wave = t >> 6, lane = t & 63;
-  const size_t rbase = (size_t)row * n_splits * G;
-#ifdef FASA_TRACE
-  unsigned long long ct[4]; ct[0] = wall_clock64();
-#endif
-  // (max, sum) pairs: wave w serves query heads w, w + 4; lane = split (+ 64 i).  Indices are
-  // clamped, not tested: the duplicates are masked below.
-  float2 ml[NG][kMaxSplitsLds / 64];
-#pragma unroll
-  for (int gi = 0; gi < NG; ++gi) {
-    const int g = min(wave + 4 * gi, G - 1);
-#pragma unroll
-    for (int i = 0; i < kMaxSplitsLds / 64; ++i) {
-      const int sp = min(lane + 64 * i, n_splits - 1);
-      ml[gi][i] = ld_agent(reinterpret_cast<const float2*>(part_ml) + (rbase + (size_t)sp * G + g));
-    }
-  }
-
-  const int part = t / C;                               // split partition of this thread
-  const int c0 = t % C;
-  const bool owner = t < P * C;
-  const float4* pa = reinterpret_cast<const float4*>(part_acc + rbase * D);
-  const int K = (n_splits + P - 1) / P;                 // splits per partition
-  f32x4_ld x[RS];
-  auto load_round = [&](int k0) {
-#pragma unroll
-    for (int u0 = 0; u0 < RS; u0 += 8) {
-      if (k0 + u0 < K) {
-#pragma unroll
-        for (int u = u0; u < u0 + 8; ++u) {
-          const int sp = min(part + P * (k0 + u), n_splits - 1);
-          agent_b128_issue(x[u], pa + (size_t)sp * C + c0);
-        }
-      }
-    }
-  };
-  load_round(0);
-
-#pragma unroll
-  for (int gi = 0; gi < NG; ++gi) {
-    const int g = wave + 4 * gi;
-    float mx = kNegBig;
-#pragma unroll
-    for (int i = 0; i < kMaxSplitsLds / 64; ++i)
-      mx = (lane + 64 * i < n_splits) ? fmaxf(mx, ml[gi][i].x) : mx;
-    mx = wave_max(mx);
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < kMaxSplitsLds / 64; ++i) {
-      const int sp = lane + 64 * i;
-      const float wgt = sp < n_splits ? exp2f(ml[gi][i].x - mx) : 0.f;
-      wsm[min(g, G - 1) * kMaxSplitsLds + sp] = wgt;   // waves beyond the group rewrite the last head's own values
-      sum = fmaf(ml[gi][i].y, wgt, sum);
-    }
-    sum = wave_sum(sum);
-    if (lane == 0 && g < G) red[g] = 1.0f / sum;
-  }
-  __syncthreads();
-#ifdef FASA_TRACE
-  ct[1] = wall_clock64();
-#endif
-
-  const int gcol = min(c0 / (D / 4), G - 1);            // query head of this thread's column
-  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int k0 = 0; k0 < K; k0 += RS) {
-    if (k0) load_round(k0);
-#pragma unroll
-    for (int u0 = 0; u0 < RS; u0 += 8) {
-      if (k0 + u0 < K) {
-        agent_b128_wait(&x[u0]);
-        // straight-line inside a chunk of 8 splits: the weight reads go out together.  A split
-        // beyond the row's count has a finite (re-read) partial and weight 0.
-        float wgt[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int sp = part + P * (k0 + u0 + u);
-          const float w0 = wsm[gcol * kMaxSplitsLds + min(sp, kMaxSplitsLds - 1)];
-          wgt[u] = sp < n_splits ? w0 : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          a.x = fmaf(x[u0 + u].x, wgt[u], a.x);
-          a.y = fmaf(x[u0 + u].y, wgt[u], a.y);
-          a.z = fmaf(x[u0 + u].z, wgt[u], a.z);
-          a.w = fmaf(x[u0 + u].w, wgt[u], a.w);
-        }
-      }
-    }
-  }
-#ifdef FASA_TRACE
-  ct[2] = wall_clock64();
-  if (t == 0 && row == 0) printf("combine: weights %llu acc %llu (x10ns) n_splits %d\n", ct[1]-ct[0], ct[2]-ct[1], n_splits);
-#endif
-  if constexpr (P > 1) {
-    float4* xb = reinterpret_cast<float4*>(xbuf);
-    if (owner && part > 0) xb[(part - 1) * C + c0] = a;
-    __syncthreads();
-    if (owner && part == 0) {
-#pragma unroll
-      for (int pp = 1; pp < P; ++pp) {
-        const float4 o = xb[(pp - 1) * C + c0];
-        a.x += o.x; a.y += o.y; a.z += o.z; a.w += o.w;
-      }
-    }
-  }
-  if (owner && part == 0) {
-    const int g = c0 / (D / 4), d4 = c0 % (D / 4);
-    const float r = red[g];
-    *reinterpret_cast<float4*>(O + ((size_t)b * Hq + (size_t)h * G + g) * D + 4 * d4) =
-        make_float4(a.x * r, a.y * r, a.z * r, a.w * r);
-  }
-}
 
 // 1-D grid of rows * n_splits workgroups, 256 threads.  A wave is 4 groups of 16 lanes; a group
 // reads one cached row per load instruction (16 lanes x 16 bytes = one 256-byte bf16 row), lane c
@@ -365,7 +212,7 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
   __syncthreads();
   if (ticket != (uint32_t)n_splits - 1u) return;
   if (t == 0) ctl[row].done_att = 0;   // clean for the next call
-  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, wsm, red, &sm_acc[0][0][0]);
+  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, n_splits, wsm, red, &sm_acc[0][0][0]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -379,8 +226,6 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
 //   logits C, lane (g = lane & 15, j): rows 4j..4j+3 of the tile for query head g
 //   V tile, lane (r = lane >> 4, c = lane & 15): head dims 8c..8c+7 of rows r, r+4, r+8, r+12
 // ---------------------------------------------------------------------------------------------
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 template <int G, bool DENSE>
 __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __restrict__ q,
@@ -419,9 +264,8 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
   const int count = DENSE ? n_ctx : seq_bsel(budget_seq, b, n_ctx, count_max);
   const int s0 = split * tok_per_split;
   const int s1 = min(count, s0 + tok_per_split);
-#ifdef FASA_TRACE
-  unsigned long long tt[8]; for (int i = 0; i < 8; ++i) tt[i] = 0; tt[0] = wall_clock64();
-#endif
+  FASA_T_DECL(5);
+  FASA_T(0);
 
   // B operands: Q^T, column g = lo (zero beyond G), k-slots (hi, 0..7) of MFMA i = dims 8(hi+4i)..+7
   bf16x8_t qb[4];
@@ -574,9 +418,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
     compute_tile(cur, jw + 64 * (n_tiles - 1));
   }
 
-#ifdef FASA_TRACE
-  tt[1] = wall_clock64();
-#endif
+  FASA_T(1);
   // ---- workgroup totals.  The four 16-lane groups of a wave hold weighted V sums over different
   // rows at one common scale (the running maximum is per head, not per group): they go to LDS as
   // they are, 16 partial sums per output, and the merge below adds them - far fewer instructions
@@ -624,23 +466,19 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
     }
   }
   if (n_splits == 1) return;
-#ifdef FASA_TRACE
-  tt[2] = wall_clock64();
-#endif
+  FASA_T(2);
   publish_barrier();
   if (t == 0) ticket = atomicAdd(&ctl[row].done_att, 1u);
   __syncthreads();
-#ifdef FASA_TRACE
-  tt[3] = wall_clock64();
-  if (t == 0 && row == 0 && split == 0) printf("attend blk0: tiles %llu merge %llu publish+ticket %llu (x10ns)\n", tt[1]-tt[0], tt[2]-tt[1], tt[3]-tt[2]);
-#endif
+  FASA_T(3);
+  FASA_T_PRINT(t == 0 && row == 0 && split == 0, "attend blk0: tiles %llu merge %llu publish+ticket %llu (x10ns)\n",
+               FASA_T_D(1, 0), FASA_T_D(2, 1), FASA_T_D(3, 2));
   if (ticket != (uint32_t)n_splits - 1u) return;
   if (t == 0) ctl[row].done_att = 0;
-  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, wsm, red, &sm_acc[0][0][0][0]);
-#ifdef FASA_TRACE
-  tt[4] = wall_clock64();
-  if (t == 0 && row == 0) printf("attend last(row0, split %d): tiles %llu merge %llu publish+ticket %llu combine %llu (x10ns)\n", split, tt[1]-tt[0], tt[2]-tt[1], tt[3]-tt[2], tt[4]-tt[3]);
-#endif
+  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, n_splits, wsm, red, &sm_acc[0][0][0][0]);
+  FASA_T(4);
+  FASA_T_PRINT(t == 0 && row == 0, "attend last(row0, split %d): tiles %llu merge %llu publish+ticket %llu combine %llu (x10ns)\n",
+               split, FASA_T_D(1, 0), FASA_T_D(2, 1), FASA_T_D(3, 2), FASA_T_D(4, 3));
 }
 
 template <typename ET, int G>

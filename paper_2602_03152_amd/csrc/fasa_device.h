@@ -21,6 +21,42 @@ __device__ __forceinline__ uint32_t score_key(float s) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Adaptive histogram bins of the fused step.  The scoring kernel predicts where a row's B-th largest
+// score will lie - mu = location + z(B/N) * scale, from a robust location and scale of a small fixed
+// sample of the row's scores and the normal quantile z - and counts every score in one of kLinBins
+// bins whose resolution is highest around that prediction; the selection reads (mu, inv = 1 / scale)
+// back and classifies with the same function, so both sides agree bit for bit.  The map is monotone
+// in s whatever mu and inv are: a poor prediction costs resolution (more candidates to resolve
+// exactly), never correctness.  With u = (s - mu) * inv, in units of the scale:
+//   |u| <= 0.75        128 bins per unit          (the threshold bin then holds N * pdf / 128 tokens)
+//   0.75 < |u| <= 2     32 bins per unit
+//   2 < |u| <= 8         4 bins per unit
+//   |u| > 8              8 bins per octave of |u|, at most 200 more
+// Few scores fall where the bins are fine, so a workgroup's 1024 scores touch only ~100 distinct bins
+// (every distinct bin is one global atomic when the workgroup's histogram is flushed).
+// ---------------------------------------------------------------------------------------------
+constexpr int kLinBins = 1024;
+__device__ __forceinline__ uint32_t lin_bin(float s, float mu, float inv) {
+#pragma clang fp contract(off)
+  const float u = (s - mu) * inv;
+  const float a = fabsf(u);
+  // every term is non-decreasing in a, and so is their rounded sum
+  const float tail = (float)min((__float_as_uint(fmaxf(a, 8.0f)) - 0x41000000u) >> 20, 200u);
+  const float g = 128.0f * fminf(a, 0.75f) + 32.0f * (fminf(fmaxf(a, 0.75f), 2.0f) - 0.75f) +
+                  4.0f * (fminf(fmaxf(a, 2.0f), 8.0f) - 2.0f) + tail;          // 0 .. 360
+  return (uint32_t)(512 + (int)floorf(copysignf(g, u)));
+}
+// z with P(Z > z) = p for a standard normal Z (rational approximation, |error| < 5e-3: it only has to
+// place the fine bins)
+__device__ __forceinline__ float normal_upper_quantile(float p) {
+  const bool flip = p > 0.5f;
+  const float pp = fmaxf(flip ? 1.0f - p : p, 1e-30f);
+  const float t = sqrtf(-2.0f * __logf(pp));
+  const float z = t - (2.30753f + 0.27061f * t) / (1.0f + t * (0.99229f + 0.04481f * t));
+  return flip ? -z : z;
+}
+
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 
 // DPP move of a 32-bit value; lanes without a source keep 0.

@@ -29,7 +29,9 @@ struct RowCtl {
   uint32_t n_cand;    // candidates collected from the threshold bin
   uint32_t done_sel;  // selection workgroups of this row that finished their slice
   uint32_t done_att;  // attention workgroups of this row that wrote their partial
-  uint32_t pad[28];
+  float bin_mu;       // adaptive histogram of the fused step: written by the scoring kernel of a call,
+  float bin_inv;      // read by its selection kernel (never has to be zero)
+  uint32_t pad[26];
 };
 static_assert(sizeof(RowCtl) == 128, "one line per row");
 
@@ -87,7 +89,7 @@ __device__ __forceinline__ int pair_dims(int pairing, int a, int b) {
 
 // Workspace carve-up (all offsets 256-byte aligned).
 struct WsLayout {
-  size_t hist_off, ctl_off, cand_off, part_acc_off, part_ml_off, tslot_off, total;
+  size_t hist_off, ctl_off, cand_off, part_acc_off, part_ml_off, rec_off, tslot_off, total;
   int rows, max_splits;
 };
 
@@ -98,6 +100,21 @@ struct AttendPlan {
 };
 
 AttendPlan plan_attend(int rows, int count, int group);
+
+// Fused selection + attention (fused.hip): tokens per workgroup and workgroups per row.
+// tpb == 0: this shape takes the staged kernels (float32 cache, everything selected, or a row longer
+// than the merge can take slices of).
+// Candidates per row of the fused step that are handed over with a record (logits of the group's query
+// heads + V row), and the bytes of workspace a row's records take.
+constexpr int kFuseRich = 64;
+constexpr size_t kFuseRecBytesPerRow = (size_t)kFuseRich * (kMaxGroup * 4 + kHeadDim * 2);
+
+struct FusePlan {
+  int tpb;
+  int nslices;
+};
+// by_sequence: lengths and budgets come from device arrays (a budget may then reach its length)
+FusePlan plan_fused(const fasa_shape& s, bool by_sequence);
 WsLayout ws_layout(const fasa_shape& s);
 
 // ---------------------------------------------------------------------------------------------
@@ -145,10 +162,12 @@ struct AppendArgs {
   PageMap pm;
 };
 constexpr AppendArgs kNoAppend = {nullptr, nullptr, nullptr, nullptr, {nullptr, 0, 0, 0}};
-// hist == nullptr: scores only
+// hist == nullptr: scores only.  adaptive_ctl != nullptr (with hist): the adaptive histogram of the
+// fused step (bins of lin_bin, location and scale left in the row counters) instead of the
+// exponent-based one the stand-alone selection reads.
 hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
                         float* S, uint32_t* hist, hipStream_t st, RaggedLens rl = {nullptr, nullptr},
-                        AppendArgs ap = kNoAppend);
+                        AppendArgs ap = kNoAppend, RowCtl* adaptive_ctl = nullptr);
 // zeroes the histogram and the row counters (workspace initialisation)
 hipError_t launch_ws_clear(const fasa_shape& s, uint32_t* hist, RowCtl* ctl, hipStream_t st);
 hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st);
@@ -161,6 +180,14 @@ hipError_t launch_attend(const fasa_shape& s, bool dense, const void* q, const v
                          const void* V, const int32_t* T, float* O, RowCtl* ctl, float* part_acc,
                          float* part_ml, hipStream_t st, RaggedLens rl = {nullptr, nullptr},
                          PageMap pm = kNoPaging);
+
+// TopK-I + FAC in one kernel after a scoring pass with the adaptive histogram (launch_score with
+// adaptive_ctl); p from plan_fused, p.tpb != 0.  The partial buffers are indexed with p.nslices splits
+// per row.  Paged caches are gathered through the table inside the kernel.
+hipError_t launch_select_attend(const fasa_shape& s, const FusePlan& p, const void* q, const void* K,
+                                const void* V, const float* S, uint32_t* hist, RowCtl* ctl, uint2* cand,
+                                int32_t* T, float* O, float* part_acc, float* part_ml, unsigned char* rec,
+                                hipStream_t st, RaggedLens rl = {nullptr, nullptr}, PageMap pm = kNoPaging);
 
 // memory-optimised variant (offload.hip)
 hipError_t launch_offload_split(const fasa_shape& s, const void* K, const int32_t* fc_idx, void* Kp,

@@ -1,6 +1,8 @@
 // TIP scoring (paper Sec. 4.1): S = (sum over the GQA group of q^dom) . k^dom for every cached
 // token, streamed from the FC-major packed copy Kp; optionally also the coarse per-row histogram
 // of the order-preserving score keys that the selection stage starts from.
+#include <type_traits>
+
 #include "fasa_device.h"
 #include "fasa_internal.h"
 
@@ -52,7 +54,18 @@ constexpr int kScoreFB = 16;  // FC planes in flight per thread
 //
 // PAIR (a fasa_pairing): the list holds FC numbers i, stored at dims (i, i + d/2) or (2i, 2i + 1),
 // or explicit dim pairs (two words per entry).
-template <typename ET, bool HIST, int NB, bool APPEND, int PAIR>
+//
+// HIST: 0 = scores only; 1 = also the per-row histogram of the top 12 bits of the score keys (what the
+// stand-alone selection kernel starts from); 2 = the adaptive histogram of the fused step: bins of
+// lin_bin(), placed by (mu, inv) from a fixed sample of 64 of the row's tokens and the row's budget - 16
+// consecutive tokens at each quarter of the row, one group per wave, the same tokens in every
+// workgroup of the row, so that all of them arrive at the same two numbers bit for bit.  The sample
+// loads go out with the loads of 1 (they only need the plane addresses); the token an APPEND call is
+// about to write is never sampled.  The workgroup of slice 0 leaves (mu, inv) in the row's counters for
+// the selection kernel.
+constexpr int kHistNone = 0, kHistKeyBits = 1, kHistAdaptive = 2;
+
+template <typename ET, int HIST, int NB, bool APPEND, int PAIR>
 __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET* Kp,
                                                     const int32_t* __restrict__ fc_idx,
                                                     float* __restrict__ S,
@@ -62,9 +75,11 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
                                                     const ET* __restrict__ k_new,
                                                     const ET* __restrict__ v_new, ET* Kc, ET* Vc,
                                                     long long sb, long long sh, long long sn,
-                                                    PageMap pm) {
+                                                    PageMap pm, RowCtl* __restrict__ ctl, int budget_max,
+                                                    const int32_t* __restrict__ budget_seq) {
   constexpr int D = kHeadDim;
   constexpr int TPT = ScoreTraits<ET>::TPT;
+  constexpr int NBINS = HIST == kHistAdaptive ? kLinBins : kHistBins;
   constexpr int NW = NB ? NB * 8 : kScoreFB;
   constexpr bool PAIRS = PAIR == FASA_PAIR_LIST;
   constexpr int PAIR_SHIFT = PAIR == FASA_PAIR_INTERLEAVED ? 1 : 0;       // FC number -> first dim
@@ -72,7 +87,8 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
   __shared__ float qsum[256];      // [t]: sum over the group of q[., t mod 128] (upper half: copies)
   __shared__ int32_t fcl[256];     // [t]: dims of list entry min(t, F - 1): lo (PAIRS: lo | hi << 8)
   __shared__ float2 qs[D / 2];
-  __shared__ uint32_t lh[HIST ? kHistBins : 1];
+  __shared__ uint32_t lh[HIST ? NBINS : 1];
+  __shared__ float2 sst[4];        // adaptive histogram: per wave, sum and sum of squares of its sample scores
   __shared__ ET knew[APPEND ? D : 1];          // the new key row
   __shared__ uint2 kpair[APPEND ? D / 2 : 1];  // per plane: the new key's (lo, hi) as stored in Kp
 
@@ -95,6 +111,23 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
   if constexpr (PAIRS) fcj = fc_idx[2 * fe + 1];
   ET newkv = ET(0);
   if constexpr (APPEND) newkv = (t < D ? k_new : v_new)[(size_t)row * D + (t & (D - 1))];
+  // sample of the adaptive histogram: wave w scores tokens w * Q .. w * Q + 15, Q = a quarter of the
+  // row rounded down to whole 64-byte lines.  Lane (token = lane mod 16, part = lane / 16) reads every
+  // fourth plane starting at plane `part`: a quarter of the loads per lane, the four parts of a token's
+  // score meeting through two lane swaps.
+  using SmpT = typename std::conditional<sizeof(ET) == 2, uint32_t, uint2>::type;
+  constexpr int NSMP = HIST == kHistAdaptive ? (NB ? NB * 2 : kScoreFB / 4) : 1;
+  SmpT smp[NSMP];
+  const int spart = (t >> 4) & 3;
+  if constexpr (HIST == kHistAdaptive) {
+    const int Ns = APPEND ? N - 1 : N;
+    const int ps = max(min((t >> 6) * ((Ns >> 2) & ~15) + (t & 15), Ns - 1), 0);
+    const ET* sp = Kp + ((size_t)row * F * n_cap + ps) * 2;
+    const int nsf = NB ? NB * 8 : min(F, kScoreFB);
+#pragma unroll
+    for (int u = 0; u < NSMP; ++u)
+      smp[u] = *reinterpret_cast<const SmpT*>(sp + (size_t)min(4 * u + spart, nsf - 1) * n_cap * 2);
+  }
   // the appended token: which workgroup and thread own it, and which of the thread's tokens it is
   const int n_app = N - 1;
   const bool own_wg = APPEND && n_app / (256 * TPT) == slice;
@@ -112,6 +145,11 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
   for (int u = 0; u < NW; ++u)
     if (NB || u < nf) w[u] = *reinterpret_cast<const uint4*>(p + (size_t)u * plane);
 
+  // adaptive histogram: where the B-th largest of N normal scores lies, in standard deviations (needs no
+  // memory: computed while the first loads are on their way)
+  float zq = 0.f;
+  if constexpr (HIST == kHistAdaptive)
+    zq = normal_upper_quantile((float)seq_bsel(budget_seq, b, N, budget_max) / (float)N);
   // ---- 3 ----  sum_g (q_g . k) = (sum_g q_g) . k, g ascending
   {
     float sum = 0.f;
@@ -130,8 +168,8 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
       if (t < D) knew[t] = newkv;
     }
   }
-  if constexpr (HIST) {
-    for (int i = t; i < kHistBins; i += 256) lh[i] = 0;
+  if constexpr (HIST != 0) {
+    for (int i = t; i < NBINS; i += 256) lh[i] = 0;
   }
   __syncthreads();
   if (t < F) {
@@ -150,6 +188,39 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
     }
   }
   __syncthreads();
+  if constexpr (HIST == kHistAdaptive) {
+    const int nsf = NB ? NB * 8 : min(F, kScoreFB);
+    float xs = 0.f;
+#pragma unroll
+    for (int u = 0; u < NSMP; ++u) {
+      const float2 qf = qs[min(4 * u + spart, nsf - 1)];
+      float lo, hi;
+      if constexpr (sizeof(ET) == 2) { lo = bf16_lo(smp[u]); hi = bf16_hi(smp[u]); }
+      else { lo = __uint_as_float(smp[u].x); hi = __uint_as_float(smp[u].y); }
+      xs = 4 * u + spart < nsf ? fmaf(qf.y, hi, fmaf(qf.x, lo, xs)) : xs;
+    }
+    xs = xor32_sum(xor16_sum(xs));   // every lane of a token now holds the token's whole sample score
+    // per wave: mean of its 16 sample scores and their mean absolute deviation from it
+    const float gm = row16_sum(xs) * (1.0f / 16.0f);
+    const float gd = row16_sum(fabsf(xs - gm)) * (1.0f / 16.0f);
+    if ((t & 63) == 0) sst[t >> 6] = make_float2(gm, gd);
+  }
+  float bin_mu = 0.f, bin_inv = 0.f;
+  if constexpr (HIST == kHistAdaptive) {
+    __syncthreads();   // the four waves' sample statistics (the K planes are still in flight)
+    // Robust against a group that holds outliers (salient tokens score far above the rest): the
+    // location is the median of the four group means, the scale the second smallest of the four group
+    // deviations, rescaled to a standard deviation (E|x - mean of 16| = 0.7725 sigma; the second
+    // smallest of four such estimates sits another 6 % lower).
+    const float2 a0 = sst[0], a1 = sst[1], a2 = sst[2], a3 = sst[3];
+    const float mmin = fminf(fminf(a0.x, a1.x), fminf(a2.x, a3.x)), mmax = fmaxf(fmaxf(a0.x, a1.x), fmaxf(a2.x, a3.x));
+    const float loc = 0.5f * ((a0.x + a1.x) + (a2.x + a3.x) - mmin - mmax);   // mean of the middle two
+    const float d01 = fminf(a0.y, a1.y), D01 = fmaxf(a0.y, a1.y), d23 = fminf(a2.y, a3.y), D23 = fmaxf(a2.y, a3.y);
+    const float second = fminf(fmaxf(d01, d23), fminf(D01, D23));             // second smallest of four
+    const float sigma = 1.373f * second;
+    bin_mu = fmaf(zq, sigma, loc);
+    bin_inv = sigma > 1e-30f ? 1.0f / sigma : 0.f;
+  }
   // the planes did not hold the appended token yet: its owner takes the pairs from LDS
   auto patch = [&](uint4& wv, int pf) {
     const uint2 kp2 = kpair[pf];
@@ -215,10 +286,15 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
       for (int k = 0; k < TPT; ++k)
         if (n0 + k < N) out[k] = acc[k];
     }
-    if constexpr (HIST) {
+    if constexpr (HIST == kHistKeyBits) {
 #pragma unroll
       for (int k = 0; k < TPT; ++k)
         if (n0 + k < N) atomicAdd(&lh[score_key(acc[k]) >> kKeyLowBits], 1u);
+    }
+    if constexpr (HIST == kHistAdaptive) {
+#pragma unroll
+      for (int k = 0; k < TPT; ++k)
+        if (n0 + k < N) atomicAdd(&lh[lin_bin(acc[k], bin_mu, bin_inv)], 1u);
     }
   }
   if constexpr (APPEND) {
@@ -227,15 +303,19 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
       *dst = newkv;
     }
   }
-  if constexpr (HIST) {
+  if constexpr (HIST == kHistAdaptive) {   // for the selection kernel (stored last: no load waits behind it)
+    if (slice == 0 && t == 0) { ctl[row].bin_mu = bin_mu; ctl[row].bin_inv = bin_inv; }
+  }
+  if constexpr (HIST != 0) {
     __syncthreads();
-    // all 16 counters of the thread are read before the first is tested: one LDS round trip, not 16
+    // all counters of the thread are read before the first is tested: one LDS round trip, not one each
+    // (a row's histogram region is kHistBins counters whichever binning fills it)
     uint32_t* gh = hist + (size_t)row * kHistBins;
-    uint32_t c[kHistBins / 256];
+    uint32_t c[NBINS / 256];
 #pragma unroll
-    for (int k = 0; k < kHistBins / 256; ++k) c[k] = lh[t + 256 * k];
+    for (int k = 0; k < NBINS / 256; ++k) c[k] = lh[t + 256 * k];
 #pragma unroll
-    for (int k = 0; k < kHistBins / 256; ++k)
+    for (int k = 0; k < NBINS / 256; ++k)
       if (c[k]) atomicAdd(&gh[t + 256 * k], c[k]);
   }
 }
@@ -273,10 +353,10 @@ __global__ __launch_bounds__(256) void hist_kernel(const float* __restrict__ S,
     if (c[k]) atomicAdd(&gh[t + 256 * k], c[k]);
 }
 
-template <typename ET, bool HIST, int NB, bool APPEND, int PAIR>
+template <typename ET, int HIST, int NB, bool APPEND, int PAIR>
 static hipError_t launch_score_v(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
                                  float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
-                                 const AppendArgs& ap) {
+                                 const AppendArgs& ap, RowCtl* ctl) {
   const int rows = s.batch * s.n_kv_heads;
   const int per_block = 256 * ScoreTraits<ET>::TPT;
   const int nslices = (s.n_ctx + per_block - 1) / per_block;
@@ -284,53 +364,60 @@ static hipError_t launch_score_v(const fasa_shape& s, const void* q, void* Kp, c
                 dim3(rows * nslices), dim3(256), st, (const ET*)q, (ET*)Kp, fc_idx, S, hist, rows, nslices,
                 s.n_q_heads, s.n_kv_heads, s.n_fc, s.n_ctx, s.n_cap, rl.n_ctx, (const ET*)ap.k_new,
                 (const ET*)ap.v_new, (ET*)ap.K, (ET*)ap.V, (long long)s.kv_stride_b, (long long)s.kv_stride_h,
-                (long long)s.kv_stride_n, ap.pm);
+                (long long)s.kv_stride_n, ap.pm, ctl, s.budget, rl.budget);
 }
 
-template <typename ET, bool HIST, bool APPEND, int PAIR>
+template <typename ET, int HIST, bool APPEND, int PAIR>
 static hipError_t launch_score_f(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
                                  float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
-                                 const AppendArgs& ap) {
+                                 const AppendArgs& ap, RowCtl* ctl) {
   switch (s.n_fc) {   // the usual settings (an eighth to a half of the FCs) get straight-line loads
-    case 8: return launch_score_v<ET, HIST, 1, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
-    case 16: return launch_score_v<ET, HIST, 2, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
-    case 24: return launch_score_v<ET, HIST, 3, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
-    case 32: return launch_score_v<ET, HIST, 4, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
-    default: return launch_score_v<ET, HIST, 0, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+    case 8: return launch_score_v<ET, HIST, 1, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
+    case 16: return launch_score_v<ET, HIST, 2, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
+    case 24: return launch_score_v<ET, HIST, 3, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
+    case 32: return launch_score_v<ET, HIST, 4, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
+    default: return launch_score_v<ET, HIST, 0, APPEND, PAIR>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
   }
 }
 
-template <typename ET, bool HIST, bool APPEND>
+template <typename ET, int HIST, bool APPEND>
 static hipError_t launch_score_h(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
                                  float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
-                                 const AppendArgs& ap) {
+                                 const AppendArgs& ap, RowCtl* ctl) {
   switch (s.pairing) {
     case FASA_PAIR_INTERLEAVED:
-      return launch_score_f<ET, HIST, APPEND, FASA_PAIR_INTERLEAVED>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+      return launch_score_f<ET, HIST, APPEND, FASA_PAIR_INTERLEAVED>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
     case FASA_PAIR_LIST:
-      return launch_score_f<ET, HIST, APPEND, FASA_PAIR_LIST>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+      return launch_score_f<ET, HIST, APPEND, FASA_PAIR_LIST>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
     default:
-      return launch_score_f<ET, HIST, APPEND, FASA_PAIR_ROTATE_HALF>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+      return launch_score_f<ET, HIST, APPEND, FASA_PAIR_ROTATE_HALF>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
   }
+}
+
+template <typename ET, bool APPEND>
+static hipError_t launch_score_a(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
+                                 float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
+                                 const AppendArgs& ap, RowCtl* ctl) {
+  if (!hist) return launch_score_h<ET, kHistNone, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
+  if (ctl) return launch_score_h<ET, kHistAdaptive, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
+  return launch_score_h<ET, kHistKeyBits, APPEND>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
 }
 
 template <typename ET>
 static hipError_t launch_score_t(const fasa_shape& s, const void* q, void* Kp, const int32_t* fc_idx,
                                  float* S, uint32_t* hist, hipStream_t st, RaggedLens rl,
-                                 const AppendArgs& ap) {
-  if (ap.k_new)
-    return hist ? launch_score_h<ET, true, true>(s, q, Kp, fc_idx, S, hist, st, rl, ap)
-                : launch_score_h<ET, false, true>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
-  return hist ? launch_score_h<ET, true, false>(s, q, Kp, fc_idx, S, hist, st, rl, ap)
-              : launch_score_h<ET, false, false>(s, q, Kp, fc_idx, S, hist, st, rl, ap);
+                                 const AppendArgs& ap, RowCtl* ctl) {
+  return ap.k_new ? launch_score_a<ET, true>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl)
+                  : launch_score_a<ET, false>(s, q, Kp, fc_idx, S, hist, st, rl, ap, ctl);
 }
 
 hipError_t launch_score(const fasa_shape& s, const void* q, const void* Kp, const int32_t* fc_idx,
-                        float* S, uint32_t* hist, hipStream_t st, RaggedLens rl, AppendArgs ap) {
+                        float* S, uint32_t* hist, hipStream_t st, RaggedLens rl, AppendArgs ap,
+                        RowCtl* adaptive_ctl) {
   // Kp is only written when a row is appended (ap.k_new != nullptr)
   return s.dtype == FASA_BF16
-             ? launch_score_t<uint16_t>(s, q, const_cast<void*>(Kp), fc_idx, S, hist, st, rl, ap)
-             : launch_score_t<float>(s, q, const_cast<void*>(Kp), fc_idx, S, hist, st, rl, ap);
+             ? launch_score_t<uint16_t>(s, q, const_cast<void*>(Kp), fc_idx, S, hist, st, rl, ap, adaptive_ctl)
+             : launch_score_t<float>(s, q, const_cast<void*>(Kp), fc_idx, S, hist, st, rl, ap, adaptive_ctl);
 }
 
 hipError_t launch_hist(const fasa_shape& s, const float* S, uint32_t* hist, hipStream_t st) {

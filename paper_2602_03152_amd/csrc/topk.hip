@@ -14,8 +14,7 @@
 //            (low 20 key bits : ~index), which is unique per token, so exactly B - |winners|
 //            candidates come out.  It then zeroes the row's histogram and counters, which leaves
 //            the workspace clean for the next call.
-#include "fasa_device.h"
-#include "fasa_internal.h"
+#include "select_common.h"
 
 namespace fasa {
 
@@ -25,181 +24,6 @@ namespace fasa {
 constexpr int kSelTokLong = 2048, kSelTokShort = 1024;
 constexpr int kSelShortMaxBlocks = 512;
 constexpr int kCandLds = 4096;                  // candidates resolved out of LDS; more: global reads
-
-__device__ __forceinline__ unsigned long long cand_composite(uint2 c) {
-  return ((unsigned long long)(c.x & ((1u << kKeyLowBits) - 1u)) << 32) | (unsigned long long)(~c.y);
-}
-
-// Block-wide search in a 4096-bin histogram of which thread t holds bins 16t .. 16t+15 in hb[]:
-// the bin b with  (entries in bins above b) < need <= (entries in bins >= b).  All 256 threads
-// call; out[0..2] = b, entries above it, entries inside it (LDS; zero if need exceeds the total,
-// the caller presets them).  Ends with a block barrier.
-__device__ __forceinline__ void find_bin_256x16(const uint32_t* hb, uint32_t need, uint32_t* wtot,
-                                                uint32_t* out) {
-  const int t = threadIdx.x;
-  uint32_t mine = 0;
-#pragma unroll
-  for (int j = 0; j < 16; ++j) mine += hb[j];
-  const uint32_t incl = block256_suffix_sum(mine, wtot);
-  uint32_t cum = incl - mine;
-  const bool owner = cum < need && need <= incl;   // true for exactly one thread of the block
-  // branch-free scan of the 16 bins from the top; the one hit is kept in registers
-  uint32_t bj = 0, ba = 0, bn = 0;
-#pragma unroll
-  for (int j = 15; j >= 0; --j) {
-    const bool hit = cum < need && cum + hb[j] >= need;
-    bj = hit ? (uint32_t)j : bj;
-    ba = hit ? cum : ba;
-    bn = hit ? hb[j] : bn;
-    cum += hb[j];
-  }
-  if (owner) {
-    out[0] = (uint32_t)(t * 16) + bj;
-    out[1] = ba;
-    out[2] = bn;
-  }
-  __syncthreads();
-}
-
-// Exact selection of the `need` largest composites among cand[0..n).  Whole block participates.
-// SHARED_SRC: the list lives in global memory and was written by other workgroups.
-// dhw: LDS scratch of 4096 counters, or null.  With it the first pass takes the top 12 bits of the
-// composite at once, which for a few hundred candidates almost always isolates the boundary
-// candidate, so that no second pass is needed; without it every pass takes 8 bits.
-// out_slot (paged caches, else null): receives the pool slot of every token written to out.
-template <bool SHARED_SRC, int NT>
-__device__ void resolve_candidates(const uint2* cand, int n, int need, int32_t* out,
-                                   uint32_t* dh /*256*/, uint32_t* wtot /*NT/64*/,
-                                   uint32_t* bc /*4: digit, need, count, out counter*/,
-                                   uint32_t* dhw, int32_t* out_slot, const PageMap& pm, int b) {
-  const int t = threadIdx.x;
-  const uint32_t out_cap = (uint32_t)need;  // never write past the row's share of T
-  unsigned long long prefix = 0;
-  int shift = 52;            // the composite has 52 significant bits: digits at 44, 36, ..., 4, 0
-  // The list is walked four entries per thread at a time, the four reads issued together (one LDS
-  // or memory round trip per chunk instead of one per entry); entry u of chunk i0 is i0 + u*NT + t.
-  constexpr int CH = 4;
-  auto load_chunk = [&](int i0, uint2 (&c)[CH]) {
-#pragma unroll
-    for (int u = 0; u < CH; ++u) {
-      const int i = min(i0 + u * NT + t, n - 1);
-      c[u] = SHARED_SRC ? ld_agent(&cand[i]) : cand[i];
-    }
-  };
-#ifdef FASA_TRACE
-  unsigned long long rt[5]; for (int i = 0; i < 5; ++i) rt[i] = wall_clock64();
-  int npass = 0;
-#endif
-  if (need < n) {
-    bool done = false;
-    if (NT == 256 && dhw != nullptr) {
-      shift = 40;            // 12-bit digit first, then 8-bit digits at 32, 24, ..., 0
-      for (int i = t; i < kHistBins; i += NT) dhw[i] = 0;
-      if (t == 0) { bc[0] = 0; bc[1] = 0; bc[2] = 0; }
-      __syncthreads();
-      for (int i0 = 0; i0 < n; i0 += CH * NT) {
-        uint2 c[CH];
-        load_chunk(i0, c);
-#pragma unroll
-        for (int u = 0; u < CH; ++u)
-          if (i0 + u * NT + t < n) atomicAdd(&dhw[(uint32_t)(cand_composite(c[u]) >> 40)], 1u);
-      }
-      __syncthreads();
-#ifdef FASA_TRACE
-      rt[1] = wall_clock64();
-#endif
-      uint32_t hb[16];
-      const uint4* hp = reinterpret_cast<const uint4*>(dhw + t * 16);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint4 v = hp[j];
-        hb[4 * j] = v.x; hb[4 * j + 1] = v.y; hb[4 * j + 2] = v.z; hb[4 * j + 3] = v.w;
-      }
-      find_bin_256x16(hb, (uint32_t)need, wtot, bc);
-      prefix = bc[0];
-      const uint32_t in_digit = bc[2];
-      need -= (int)bc[1];
-      done = (uint32_t)need == in_digit;     // everything under this prefix is a winner
-      __syncthreads();                       // bc is rewritten by the passes below
-#ifdef FASA_TRACE
-      rt[2] = wall_clock64();
-#endif
-    }
-    while (!done && shift > 0) {
-      const int width = shift >= 8 ? 8 : shift;   // the last digit is the 4 bits left over
-      shift -= width;
-#ifdef FASA_TRACE
-      ++npass;
-#endif
-      if (t < 256) dh[t] = 0;
-      __syncthreads();
-      for (int i0 = 0; i0 < n; i0 += CH * NT) {
-        uint2 c[CH];
-        load_chunk(i0, c);
-#pragma unroll
-        for (int u = 0; u < CH; ++u) {
-          const unsigned long long cc = cand_composite(c[u]);
-          if (i0 + u * NT + t < n && (cc >> (shift + width)) == prefix)
-            atomicAdd(&dh[(uint32_t)(cc >> shift) & ((1u << width) - 1u)], 1u);
-        }
-      }
-      __syncthreads();
-      const uint32_t cnt = t < 256 ? dh[t] : 0u;
-      const uint32_t incl = block_suffix_sum<NT>(cnt, wtot);
-      const uint32_t excl = incl - cnt;
-      if (t < 256 && excl < (uint32_t)need && (uint32_t)need <= incl) {
-        bc[0] = (uint32_t)t;
-        bc[1] = (uint32_t)need - excl;
-        bc[2] = cnt;
-      }
-      __syncthreads();
-      prefix = (prefix << width) | bc[0];
-      need = (int)bc[1];
-      const uint32_t in_digit = bc[2];
-      // no barrier needed here: bc is next written three barriers into the following pass
-      if ((uint32_t)need == in_digit) break;  // everything under this prefix is a winner
-    }
-  } else {
-    shift = 52;  // take all: (c >> 52) == 0 >= 0
-  }
-#ifdef FASA_TRACE
-  rt[3] = wall_clock64();
-#endif
-  // output: one position atomic per wave and chunk (ballots give every taken entry its offset)
-  for (int i0 = 0; i0 < n; i0 += CH * NT) {
-    uint2 c[CH];
-    load_chunk(i0, c);
-    unsigned long long m[CH];
-    uint32_t taken = 0;
-#pragma unroll
-    for (int u = 0; u < CH; ++u) {
-      m[u] = __ballot(i0 + u * NT + t < n && (cand_composite(c[u]) >> shift) >= prefix);
-      taken += (uint32_t)__popcll(m[u]);
-    }
-    int sl[CH];
-    if (out_slot) {   // paged cache: where the rows live; looked up before the stores below
-#pragma unroll
-      for (int u = 0; u < CH; ++u) sl[u] = kv_slot(pm, b, (int)(c[u].y & 0x7fffffffu));
-    }
-    uint32_t pos = 0;
-    if (lane_id() == 0 && taken) pos = atomicAdd(&bc[3], taken);
-    pos = (uint32_t)__builtin_amdgcn_readfirstlane((int)pos);
-#pragma unroll
-    for (int u = 0; u < CH; ++u) {
-      const uint32_t mine = pos + __builtin_amdgcn_mbcnt_hi((uint32_t)(m[u] >> 32),
-                                                            __builtin_amdgcn_mbcnt_lo((uint32_t)m[u], 0u));
-      if (((m[u] >> lane_id()) & 1ull) && mine < out_cap) {
-        out[mine] = (int32_t)c[u].y;
-        if (out_slot) out_slot[mine] = sl[u];
-      }
-      pos += (uint32_t)__popcll(m[u]);
-    }
-  }
-#ifdef FASA_TRACE
-  rt[4] = wall_clock64();
-  if (t == 0 && blockIdx.x < 64) printf("resolve: widehist %llu findbin %llu passes(%d) %llu output %llu (x10ns)\n", rt[1]-rt[0], rt[2]-rt[1], npass, rt[3]-rt[2], rt[4]-rt[3]);
-#endif
-}
 
 // 1-D grid of rows * nslices workgroups, nslices = ceil(N / TPB), TPB tokens per workgroup
 template <int TPB>
@@ -227,9 +51,8 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   const int bsel = seq_bsel(budget_seq, row / Hkv, N, budget_max);
   const float* s = S + (size_t)row * n_cap;
   const int base = slice * kSelTokPerBlock;
-#ifdef FASA_TRACE
-  unsigned long long tt[8]; for (int i = 0; i < 8; ++i) tt[i] = 0; tt[0] = wall_clock64();
-#endif
+  FASA_T_DECL(6);
+  FASA_T(0);
 
   // ---- this workgroup's scores: loads go out first, the histogram work hides their latency ----
   float v[kSelPerThread];
@@ -256,13 +79,11 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
       const uint4 x = hp[j];
       hb[4 * j] = x.x; hb[4 * j + 1] = x.y; hb[4 * j + 2] = x.z; hb[4 * j + 3] = x.w;
     }
-    find_bin_256x16(hb, (uint32_t)bsel, wtot, thr);   // its first barrier orders the zeroing of thr
+    find_bin_256<16>(hb, (uint32_t)bsel, wtot, thr);   // its first barrier orders the zeroing of thr
   }
   const uint32_t tbin = thr[0];
   const uint32_t n_above = thr[1];
-#ifdef FASA_TRACE
-  tt[1] = wall_clock64();
-#endif
+  FASA_T(1);
 
   // ---- classify, then one position range per workgroup and counter ----
   uint32_t key[kSelPerThread];
@@ -295,9 +116,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
     bc[1] = (uint32_t)(old >> 32);
   }
   __syncthreads();
-#ifdef FASA_TRACE
-  tt[2] = wall_clock64();
-#endif
+  FASA_T(2);
   uint32_t bw = bc[0] + pw, bcand = bc[1] + pc;
   int32_t* trow = T + (size_t)row * t_pitch;
   uint2* crow = cand + (size_t)row * n_cap;
@@ -321,10 +140,9 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
   __syncthreads();
   const bool last = bc[2] == (uint32_t)nslices - 1u;
   __syncthreads();
-#ifdef FASA_TRACE
-  tt[3] = wall_clock64();
-  if (!last && t == 0 && row == 0 && slice == 0) printf("select blk0: thr %llu pos %llu ticket %llu (x10ns)\n", tt[1]-tt[0], tt[2]-tt[1], tt[3]-tt[2]);
-#endif
+  FASA_T(3);
+  FASA_T_PRINT(!last && t == 0 && row == 0 && slice == 0, "select blk0: thr %llu pos %llu ticket %llu (x10ns)\n",
+               FASA_T_D(1, 0), FASA_T_D(2, 1), FASA_T_D(3, 2));
   if (!last) return;
   // the candidates are exactly the tokens of the threshold bin: their number is in the histogram
   const int n_cand = (int)min(thr[2], (uint32_t)n_cap);
@@ -343,18 +161,15 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ S
     }
   }
   __syncthreads();
-#ifdef FASA_TRACE
-  tt[4] = wall_clock64();
-#endif
+  FASA_T(4);
   // with <= 2048 candidates the upper half of lc is free: 4096 counters for a 12-bit first digit
   uint32_t* dhw = n_cand <= kCandLds / 2 ? reinterpret_cast<uint32_t*>(lc + kCandLds / 2) : nullptr;
   int32_t* sout = srow ? srow + n_above : nullptr;
-  if (in_lds) resolve_candidates<false, 256>(lc, n_cand, need, trow + n_above, dh, wtot, bc, dhw, sout, pm, row / Hkv);
-  else resolve_candidates<true, 256>(crow, n_cand, need, trow + n_above, dh, wtot, bc, nullptr, sout, pm, row / Hkv);
-#ifdef FASA_TRACE
-  tt[5] = wall_clock64();
-  if (t == 0 && row == 0) printf("select last(row0,slice %d): thr %llu pos %llu ticket %llu candload %llu resolve %llu ncand %d need %d (x10ns)\n", slice, tt[1]-tt[0], tt[2]-tt[1], tt[3]-tt[2], tt[4]-tt[3], tt[5]-tt[4], n_cand, need);
-#endif
+  if (in_lds) resolve_candidates<false, 256, 52>(lc, n_cand, need, trow + n_above, dh, wtot, bc, dhw, sout, pm, row / Hkv);
+  else resolve_candidates<true, 256, 52>(crow, n_cand, need, trow + n_above, dh, wtot, bc, nullptr, sout, pm, row / Hkv);
+  FASA_T(5);
+  FASA_T_PRINT(t == 0 && row == 0, "select last(row0,slice %d): thr %llu pos %llu ticket %llu candload %llu resolve %llu ncand %d need %d (x10ns)\n",
+               slice, FASA_T_D(1, 0), FASA_T_D(2, 1), FASA_T_D(3, 2), FASA_T_D(4, 3), FASA_T_D(5, 4), n_cand, need);
 
   // leave the row's histogram and counters zeroed for the next call
   {

@@ -1,51 +1,47 @@
 """The one place where the library issues loads the compiler does not track: the 16-byte agent-scope
 loads of the split merge (inline assembly, because the language's atomic loads stop at 8 bytes).  Their
-destination registers may only be touched after the explicit wait that follows them.  This test compiles
-the attention source to device assembly with the library's own flags and checks exactly that, for every
-kernel instance, so a compiler that schedules differently is caught on the host."""
+destination registers may only be touched after the explicit wait that follows them.  The build itself
+checks that in the generated assembly (paper_2602_03152_amd/build.py, check_untracked_loads); here the
+checker is pinned on small listings - it must find a planted violation on a side path and must not
+flag a block that merely follows the loads in the text - and run on the real sources."""
 import os
-import re
 import shutil
-import subprocess
 
 import pytest
 
 from paper_2602_03152_amd import build as B
 
+GOOD = """
+kern:
+\tv_mov_b32_e32 v1, v0
+\t;;#ASMSTART
+\tglobal_load_dwordx4 v[4:7], v[2:3], off sc1
+\t;;#ASMEND
+\ts_cbranch_execz .LBB0_2
+\tv_add_u32_e32 v9, v1, v1
+.LBB0_2:
+\t;;#ASMSTART
+\ts_waitcnt vmcnt(0)
+\t;;#ASMEND
+\tv_add_f32_e32 v8, v4, v5
+\ts_branch .LBB0_4
+.LBB0_3:
+\tv_mov_b32_e32 v4, 0
+.LBB0_4:
+\ts_endpgm
+"""
+
+
+def test_checker_follows_the_control_flow_graph():
+    loads, waits, bad = B.check_untracked_loads(GOOD)
+    assert (loads, waits, bad) == (1, 1, [])          # .LBB0_3 touches v4 but is not reachable from the load
+    planted = GOOD.replace("\tv_add_u32_e32 v9, v1, v1", "\tv_add_u32_e32 v9, v6, v1")   # side path reads v6 early
+    assert [b[1] for b in B.check_untracked_loads(planted)[2]] == ["v_add_u32_e32 v9, v6, v1"]
+    unwaited = GOOD.replace("\ts_waitcnt vmcnt(0)", "\ts_nop 0")
+    assert B.check_untracked_loads(unwaited)[2]
+
 
 @pytest.mark.skipif(shutil.which(B.HIPCC) is None and not os.path.exists(B.HIPCC), reason="no hipcc")
-def test_untracked_loads_are_waited_for_before_any_use(tmp_path):
-    out = tmp_path / "attend_dev.s"
-    flags = [f for f in B.FLAGS if f != "-fPIC"]
-    p = subprocess.run([B.HIPCC, *flags, "--cuda-device-only", "-S", os.path.join(B.CSRC, "attend.hip"), "-o", str(out)],
-                       stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    assert p.returncode == 0, p.stdout[-2000:]
-    pending, loads, waits, touches = set(), 0, 0, []
-    in_asm = False
-    for ln, line in enumerate(out.read_text().split("\n"), 1):
-        if "ASMSTART" in line:
-            in_asm = True
-            continue
-        if "ASMEND" in line:
-            in_asm = False
-            continue
-        if in_asm:
-            m = re.search(r"global_load_dwordx4 v\[(\d+):(\d+)\].*\bsc1\b", line)
-            if m:
-                pending.update(range(int(m.group(1)), int(m.group(2)) + 1))
-                loads += 1
-            elif "s_waitcnt vmcnt(0)" in line:
-                pending.clear()
-                waits += 1
-            continue
-        if "s_endpgm" in line:
-            assert not pending, "kernel ends with unwaited loads (line %d)" % ln
-        if pending and re.match(r"\s+(v_|ds_|global_|flat_|buffer_|scratch_)", line):
-            regs = set()
-            for a, b in re.findall(r"v\[(\d+):(\d+)\]", line):
-                regs.update(range(int(a), int(b) + 1))
-            regs.update(int(a) for a in re.findall(r"\bv(\d+)\b", line))
-            if regs & pending:
-                touches.append((ln, line.strip()))
-    assert loads > 0 and waits > 0, "the merge no longer uses the 16-byte agent-scope loads: drop this test"
-    assert not touches, touches[:5]
+@pytest.mark.parametrize("source", B.ASM_CHECKED)
+def test_untracked_loads_are_waited_for_before_any_use(tmp_path, source):
+    B._check_asm(source, (), str(tmp_path), False)       # raises on a violation
