@@ -20,29 +20,35 @@ def fb():
 
 
 def check_selection(S_ref, D_ref, T_gpu, budget, n_ctx):
-    """The selected set must contain every token whose oracle score clears the oracle's B-th
-    score by more than the band and none that falls short of it by more than the band;
-    band = 1e-5 * max(|tau|, max_n D[n]) (the score tolerance, applied at the threshold).
-    Returns the number of tokens on which the set differs from the oracle's own."""
+    """Index sets against the oracle's (float64 scores rounded to float32, then ranked): the sets must be
+    equal except for tokens whose oracle score lies within the score tolerance of the oracle's B-th
+    score tau.  Per token n the band is what two float32 evaluations of S[n] and of tau may differ by:
+        |S_ref[n] - tau| <= 1e-5 * (max(|S_ref[n]|, D[n]) + max(|tau|, D[token of tau]))
+    (D = sum of absolute terms of the dot product: each side's error bound is 1e-5 times its own
+    max(|S|, D), the bound the score test itself enforces).  Returns the number of differing tokens."""
     bsel = min(budget, n_ctx)
     n_diff = 0
     for b in range(S_ref.shape[0]):
         for h in range(S_ref.shape[1]):
             s = S_ref[b, h, :n_ctx]
+            dd = D_ref[b, h, :n_ctx]
             t = np.asarray(T_gpu[b, h])
             assert t.shape == (bsel,)
             assert t.min() >= 0 and t.max() < n_ctx
             assert len(np.unique(t)) == bsel, "duplicates in the index set"
             ref = O.topk_indices(s.astype(np.float32), budget)
-            tau = np.sort(s)[n_ctx - bsel]
-            band = SCORE_RTOL * max(abs(tau), float(D_ref[b, h, :n_ctx].max()))
-            sel = np.zeros(n_ctx, bool); sel[t] = True
-            must = s > tau + band
-            must_not = s < tau - band
-            assert sel[must].all(), "a clear winner is missing"
-            assert not sel[must_not].any(), "a clear loser was selected"
-            n_diff += int(np.setdiff1d(ref, t).size)
+            i_tau = ref[np.argmin(s[ref])]                     # the oracle's B-th token
+            tau = s[i_tau]
+            differ = np.setxor1d(ref, t)
+            band = SCORE_RTOL * (np.maximum(np.abs(s[differ]), dd[differ]) + max(abs(tau), dd[i_tau]))
+            assert np.all(np.abs(s[differ] - tau) <= band), "a token outside the tie band differs from the oracle's set"
+            n_diff += int(differ.size) // 2
     return n_diff
+
+
+def check_selection_exact(S_gpu_f32, T_gpu, budget, n_ctx):
+    """Band-free: on the device's own float32 scores the set is THE top-B set (ties to the lower index)."""
+    np.testing.assert_array_equal(np.sort(np.asarray(T_gpu), axis=-1), O.topk(S_gpu_f32[:, :, :n_ctx], budget, n_ctx))
 
 
 def run_step(fb, w, x, d=None, k_new=None, v_new=None, q=None, n_ctx=None, budget=None, pairing="half"):
@@ -71,6 +77,7 @@ def compare_step(w, x_host_q, K, V, fc_idx, d, n_ctx, budget, rows=None, pairing
     assert np.all(err <= SCORE_RTOL * np.maximum(np.abs(S_ref), D_ref))
     # T is [batch][n_kv_heads][bsel] packed at the front of the buffer (row pitch = bsel of this call)
     T = to_host(d.T).reshape(-1)[: w.batch * w.n_kv_heads * bsel].reshape(w.batch, w.n_kv_heads, bsel)[bs]
+    check_selection_exact(to_host(d.S)[bs], T, budget, n_ctx)
     n_diff = check_selection(S_ref, D_ref, T, budget, n_ctx)
     O_ref = O.sparse_attend(q, K[bs], V[bs], T)          # oracle FAC on the device's validated set
     o_err = np.abs(to_host(d.O)[bs].astype(np.float64) - O_ref).max()
@@ -108,6 +115,44 @@ def test_decode_step_reduced(fb, name):
     w = W.WORKLOADS[cid].scaled(**kw)
     x = W.make_inputs(w, n_cap=(w.n_ctx + 63) // 64 * 64)
     print("decode_step", name, flush=True)
+    d = run_step(fb, w, x)
+    n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget)
+    print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
+
+
+def _tied_inputs(w, n_classes, seed):
+    """Inputs whose keys come from only `n_classes` distinct vectors: the scores then take few distinct
+    values with many exact ties, so the threshold bin of the selection holds a whole class of tokens
+    (the degenerate distributions the selection's fallback paths exist for)."""
+    x = W.make_inputs(w, n_cap=(w.n_ctx + 63) // 64 * 64)
+    rng = np.random.default_rng(seed)
+    cls = rng.integers(0, n_classes, size=(w.batch, w.n_kv_heads, w.n_ctx))
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            proto = x["K"][b, h, :n_classes].copy()          # the first n_classes drawn keys are the prototypes
+            x["K"][b, h, :w.n_ctx] = proto[cls[b, h]]
+    return x
+
+
+@pytest.mark.parametrize("name,kw,n_classes", [
+    # every token the same key: all N scores tie, the threshold bin is the whole row (global resolve)
+    ("all_equal", dict(n_ctx=5000, budget=300), 1),
+    # ~600 tokens per score value: the radix resolve in LDS
+    ("classes_8", dict(n_ctx=5000, budget=700), 8),
+    # ~125 per value: ranking by counting, the taken rows gathered by the merging workgroup
+    ("classes_40", dict(n_ctx=5000, budget=300), 40),
+    # ~20 per value in one workgroup: few enough for records, too many for one workgroup to carry
+    ("classes_50_one_slice", dict(n_ctx=1000, budget=110), 50),
+    # a handful per value: the record path with exact ties inside it
+    ("classes_300", dict(n_ctx=2500, budget=200), 300),
+    ("classes_8_gqa7", dict(cid=3, batch=1, n_ctx=3000, budget=500), 8),
+    ("all_equal_long", dict(n_ctx=70000, budget=3000, n_kv_heads=1, n_q_heads=4), 1),
+])
+def test_decode_step_tied_scores(fb, name, kw, n_classes):
+    kw = dict(kw); cid = kw.pop("cid", 1)
+    w = W.WORKLOADS[cid].scaled(**kw)
+    x = _tied_inputs(w, n_classes, seed=len(name))
+    print("tied scores", name, flush=True)
     d = run_step(fb, w, x)
     n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget)
     print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
@@ -319,6 +364,54 @@ def test_full_size_sampled(fb, cid, rows):
     d = run_step(fb, w, x)
     n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget, rows=rows)
     print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
+
+
+def test_full_size_growing_cache(fb):
+    """The long-CoT workload as the benchmark runs it: 512 consecutive steps on ONE cache at full size
+    (batch 8, GQA 7, 32768 -> 33280 tokens), each appending one K/V row per (b, h) inside the scoring
+    kernel and selecting 18.9 % of the new length, one workspace for the whole loop.  The oracle checks
+    steps 0, 1, 255 and 511 on two batch entries; after the loop every appended position of K, V and
+    of the packed copy must hold exactly what was appended, and nothing else may have changed."""
+    from tests.gpu_util import Device, to_dev, to_host
+    w = W.WORKLOADS[3]
+    steps, n0 = 512, w.n_ctx
+    n_cap = (n0 + steps + 63) // 64 * 64
+    print("growing cache at full size: drawing inputs", flush=True)
+    x = W.make_inputs(w, n_cap=n_cap)
+    K, V = x["K"].copy(), x["V"].copy()
+    d = Device(w, x)
+    d.T = torch.full((w.batch, w.n_kv_heads, W.budget_fraction(n0 + steps)), -1, dtype=torch.int32, device="cuda")
+    d.ws_bytes = max(fb.fasa_workspace_bytes(d.make_shape(n_ctx=n0 + s, budget=W.budget_fraction(n0 + s)))
+                     for s in (0, steps))
+    d.ws = torch.full((d.ws_bytes,), 0x77, dtype=torch.uint8, device="cuda")
+    fb.fasa_workspace_init(d.shape, d.ws, d.ws_bytes)
+    d.pack()
+    kp0 = to_host(d.Kp, d.st).copy()
+    rows = [0, 5]
+    checked = (0, 1, 255, 511)
+    n = n0
+    run_step(fb, w, x, d=d, n_ctx=n, budget=W.budget_fraction(n))
+    compare_step(w, x["q"], K, V, x["fc_idx"], d, n, W.budget_fraction(n), rows=rows)
+    for s in range(1, steps):
+        a = W.make_append(w, x["fc_idx"], step=s, n_before=n)
+        K[:, :, n] = a["k_new"]; V[:, :, n] = a["v_new"]
+        n += 1
+        shape = d.make_shape(n_ctx=n, budget=W.budget_fraction(n))
+        fb.fasa_decode_step(shape, to_dev(a["q"]), d.K, d.V, d.Kp, d.fc_idx, to_dev(a["k_new"]), to_dev(a["v_new"]),
+                            d.S, d.T, d.O, d.ws, d.ws_bytes)
+        if s in checked:
+            torch.cuda.synchronize()
+            print("  step", s, "n", n, "budget", W.budget_fraction(n), flush=True)
+            compare_step(w, a["q"], K, V, x["fc_idx"], d, n, W.budget_fraction(n), rows=rows)
+    torch.cuda.synchronize()
+    assert n == n0 + steps - 1
+    np.testing.assert_array_equal(to_host(d.K, d.st), K)
+    np.testing.assert_array_equal(to_host(d.V, d.st), V)
+    kp = to_host(d.Kp, d.st)
+    ref_new = O.pack_kcache(K[:, :, n0:n], x["fc_idx"], n - n0)           # the appended tokens only
+    np.testing.assert_array_equal(kp[:, :, :, n0:n], ref_new)
+    np.testing.assert_array_equal(kp[:, :, :, :n0], kp0[:, :, :, :n0])
+    np.testing.assert_array_equal(kp[:, :, :, n:], kp0[:, :, :, n:])
 
 
 def test_million_token_context(fb):
