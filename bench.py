@@ -3,20 +3,24 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
 
-A "step" is one fasa_decode_step (score -> top-k -> sparse attention) over one batch of synthetic,
-HBM-resident input shaped like the chosen workload (default: the Llama-3-8B-shaped layer at 32k
-context, budget 2048, 16 dominant FCs).  The step rotates over R independent buffer sets so that the
-bytes a step touches have left the 256 MB last-level cache before their set comes round again.
+A "step" is one fasa_decode_step (scores + histogram, then selection and sparse attention in one
+kernel) over one batch of synthetic, HBM-resident input shaped like the chosen workload (default: the
+Llama-3-8B-shaped layer at 32k context, budget 2048, 16 dominant FCs).  The step rotates over R
+independent buffer sets so that the bytes a step touches have left the 256 MB last-level cache before
+their set comes round again.
 
-Three passes, all inside this process:
-  timed     W warm-up + exactly K steps replayed from a captured HIP graph (one graph = one step on
-            each of the R buffer sets), bracketed by synchronize; `value` = microseconds per step.
-            The same K steps launched eagerly are timed too and reported as `eager_us_per_step`.
-  kernels   the same K steps launched eagerly with the library's per-kernel timestamps on: average
-            GPU execution time of every kernel of the path -> the `roofline` object of the dominant
-            kernel and the `kernels` table.
-  baselines the library's own full-KV decode kernel on the same buffers (`dense_baseline`) and the
-            CPU oracle timed on the host cores (`cpu_baseline`).
+Passes, all inside this process:
+  timed      W warm-up + exactly K steps launched eagerly on one stream, bracketed by synchronize;
+             `value` = microseconds per step, `step_roofline` = the step's algorithmic bytes over that
+             time against the HBM peak.  The same steps as one captured HIP graph are timed too
+             (`graph_us_per_step`), every replay checked against the eager result.
+  kernels    the same K steps with the library's per-kernel timestamps on: average GPU execution time
+             of every kernel of the path -> `kernels`; `roofline` describes the kernel that takes the
+             longest.  `traffic` quotes the HBM bytes per launch measured with rocprofv3 counters
+             (profiles/), only while the kernel sources are the ones they were measured on.
+  baselines  the library's own full-KV decode kernel on the same buffers (`dense_baseline`) and the
+             CPU oracle timed on the host cores (`cpu_baseline`).
+  others     the remaining workload shapes, timed briefly (`other_workloads`).
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
 from __future__ import annotations
@@ -38,6 +42,7 @@ LLC_BYTES = 256 << 20         # last-level (memory-side) cache the rotation has 
 # what the same counters read for a plain copy kernel of known size (see profiles/).  Keyed by
 # (workload config id, kernel name); bytes per launch.  None = not measured yet.
 MEASURED_TRAFFIC = {
+    "source_hash": "unmeasured",   # source_hash() of the kernels the counters were taken on
     # profiles/decode_step_llama3_8b_layer_n32768_b2048_hbm_counters.txt
     (1, "fasa_score_hist"): 16876270 + 1235328,
     (1, "fasa_select"): 1393282 + 350168,
@@ -512,6 +517,11 @@ def main():
     ap.add_argument("--stage-timers", action="store_true",
                     help="with FASA_LIB pointing at the traced library (python -m paper_2602_03152_amd.build --trace): "
                          "run three steps and let the kernels print their phase times for row 0; nothing is timed")
+    ap.add_argument("--other-workloads", default="3,4,2",
+                    help="default mode: workload ids timed briefly after the headline one and reported under "
+                         "other_workloads (empty string: none)")
+    ap.add_argument("--other-budget-s", type=float, default=150.0,
+                    help="no further workload of --other-workloads is started once the run has taken this long")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only plain device copies of known size (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -552,9 +562,118 @@ def main():
         return paged(args, w, fb, W, np, torch)
     if args.recall_table:
         return recall_table(args, w, fb, W, np, torch)
+    if args.stage_timers:
+        return stage_timers(args, w, fb, W, np, torch)
+
+    t_start = time.time()
+    head = measure(args, w, fb, W, np, torch, steps=args.steps, warmup=args.warmup, full=True)
+    # ---------------- the other workloads at a 32k+ context (and the batch one), briefly ----------------
+    others = {}
+    for cid in [int(c) for c in args.other_workloads.split(",") if c.strip()]:
+        if cid == w.config_id or cid not in W.WORKLOADS:
+            continue
+        if time.time() - t_start > args.other_budget_s:
+            log("other workloads: time budget used up, skipping config %d" % cid)
+            continue
+        wo = W.WORKLOADS[cid]
+        r = measure(args, wo, fb, W, np, torch, steps=min(args.steps, 100), warmup=min(args.warmup, 10), full=False)
+        others[wo.name] = {"us_per_step": r["us_per_step"], "steps": r["timed_steps"], "alg_bytes": r["model"]["alg"],
+                           "step_frac_of_peak": round(r["model"]["alg"] / r["us_per_step"] / 1e3 / HBM_PEAK_GBPS, 4),
+                           "kernels_avg_us": {k: v["avg_us"] for k, v in r["kernels"].items()},
+                           "dominant_kernel": r["roofline"]["kernel"], "dominant_kernel_frac": r["roofline"]["frac"]}
+    us = head["us_per_step"]
+    model = head["model"]
+    out = {
+        "metric": "us_per_decode_step", "value": round(us, 3), "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "timed_steps": head["timed_steps"], "warmup": args.warmup,
+        "ms_per_step": round(us / 1e3, 6),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        # storage and matrix-core input type; every sum is accumulated in float32
+        "dtype": w.dtype, "accum_dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "n_ctx": w.n_ctx, "budget": min(w.budget, w.n_ctx), "n_fc": w.n_fc,
+                   "storage_dtype": w.dtype, "pairing": args.pairing, "buffer_sets": head["buffer_sets"],
+                   "launch": "eager"},
+        # the whole step against the HBM roofline: what the benchmark spec's target is about
+        "step_roofline": {"bound": "hbm", "bytes": model["alg"], "us": round(us, 3),
+                          "achieved": round(model["alg"] / us / 1e3, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                          "frac": round(model["alg"] / us / 1e3 / HBM_PEAK_GBPS, 4)},
+        "hbm": {"alg_bytes": model["alg"], "alg_plus_intermediate_bytes": model["alg_plus_intermediates"],
+                # the same with the intermediates (S written and re-read, T) counted: the bytes actually touched
+                "step_touched_gbps": round(model["alg_plus_intermediates"] / us / 1e3, 1),
+                "step_touched_frac_of_peak": round(model["alg_plus_intermediates"] / us / 1e3 / HBM_PEAK_GBPS, 4),
+                "kernel_time_gbps": round(model["alg"] / head["sum_kernel_us"] / 1e3, 1),
+                # second denominator: what a plain 256 MiB device copy moves (read + write) on this machine
+                "copy_ceiling_gbps": head["copy_gbps"]},
+        "step_us_percentiles": head["step_pct"],
+        "graph_us_per_step": head["graph_us"], "graph_steps": head["graph_steps"],
+        "graph_replays_match_eager": head["graph_ok"],
+        "sum_kernel_us": round(head["sum_kernel_us"], 3),
+        "roofline": head["roofline"],
+        "kernels": head["kernels"],
+        "dense_baseline": head["dense_baseline"],
+        "selection_recall_vs_full_head": head["recall"],
+        "other_workloads": others,
+        "cpu_baseline": head["cpu"],
+    }
+    print(json.dumps(out), flush=True)
+
+
+def stage_timers(args, w, fb, W, np, torch):
+    """Three steps on one buffer set with the traced library (FASA_LIB): the kernels print their phases."""
+    x = W.make_inputs(w)
+    dev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+    tdt = torch.int16 if w.dtype == "bf16" else torch.float32
+    n_cap, bsel = x["n_cap"], min(w.budget, w.n_ctx)
+    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_fc, w.n_ctx, n_cap, w.budget, w.dtype)
+    q, K, V, fc = dev(x["q"]), dev(x["K"]), dev(x["V"]), dev(x["fc_idx"])
+    Kp = torch.zeros((w.batch, w.n_kv_heads, w.n_fc, n_cap, 2), dtype=tdt, device="cuda")
+    S = torch.zeros((w.batch, w.n_kv_heads, n_cap), dtype=torch.float32, device="cuda")
+    T = torch.zeros((w.batch, w.n_kv_heads, bsel), dtype=torch.int32, device="cuda")
+    O = torch.zeros((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    ws_bytes = fb.fasa_workspace_bytes(shape)
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+    fb.fasa_workspace_init(shape, ws, ws_bytes)
+    fb.fasa_pack_kcache(shape, K, fc, Kp, 0, w.n_ctx)
+    for i in range(3):
+        fb.fasa_decode_step(shape, q, K, V, Kp, fc, None, None, S, T, O, ws, ws_bytes)
+        torch.cuda.synchronize()
+        print("---- step %d ----" % i, flush=True)
+
+
+def source_hash():
+    """Hash of the kernel sources: measured HBM traffic is only quoted for the sources it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2602_03152_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")) and name != "floors.hip":
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(config_id, kernel):
+    """Bytes per launch from the rocprofv3 --pmc runs under profiles/, or None if the kernels changed since."""
+    if MEASURED_TRAFFIC.get("source_hash") != source_hash():
+        if not measured_traffic.warned:
+            log("bench: kernel sources differ from the ones the HBM counters in profiles/ were taken on: traffic = null")
+            measured_traffic.warned = True
+        return None
+    return MEASURED_TRAFFIC.get((config_id, kernel))
+
+
+measured_traffic.warned = False
+
+
+def measure(args, w, fb, W, np, torch, steps, warmup, full):
+    """Times `steps` decode steps of workload w (after `warmup`), rotating over R HBM-resident buffer sets;
+    then per-kernel GPU times.  full: also the captured graph, single-step percentiles, the copy ceiling,
+    the dense baseline, the selection recall and the CPU oracle."""
     rows = w.batch * w.n_kv_heads
     model = W.algorithmic_bytes(w)
     bsel = min(w.budget, w.n_ctx)
+    e = w.elem_bytes
 
     # ---------------- inputs: one seeded draw, cloned into R device-resident sets ----------------
     t0 = time.time()
@@ -563,12 +682,11 @@ def main():
         x = W.as_interleaved(x)
     elif args.pairing == "list":
         x["fc_idx"] = W.explicit_pairs(x["fc_idx"], w.head_dim)
-    log("inputs drawn in %.1fs" % (time.time() - t0))
+    log("%s: inputs drawn in %.1fs" % (w.name, time.time() - t0))
     n_cap = x["n_cap"]
     tdt = torch.int16 if w.dtype == "bf16" else torch.float32
     touched = model["alg_plus_intermediates"]
     R = args.sets or max(4, min(64, int(np.ceil(2.5 * LLC_BYTES / touched))))
-    K_steps = max(R, (args.steps // R) * R) if not args.no_graph else args.steps
     dev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
     shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_fc, w.n_ctx, n_cap, w.budget, w.dtype,
                           pairing=args.pairing)
@@ -598,13 +716,6 @@ def main():
     def dense(s):
         fb.fasa_dense_attend(shape, s["q"], s["K"], s["V"], s["O"], s["ws"], ws_bytes)
 
-    if args.stage_timers:
-        for i in range(3):
-            step(sets[0])
-            torch.cuda.synchronize()
-            print("---- step %d ----" % i, flush=True)
-        return
-
     def time_loop(fn, n_steps, warm):
         for i in range(warm):
             fn(sets[i % R])
@@ -617,13 +728,17 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n_steps * 1e3          # us per step
 
-    # ---------------- pass 1: timed region ----------------
-    eager_us = time_loop(step, K_steps, args.warmup)
-    log("eager: %.2f us/step" % eager_us)
-    ref_T = np.sort(sets[0]["T"].cpu().numpy(), -1)
-    ref_O = sets[0]["O"].cpu().numpy().copy()
-    graph_us, mode = None, "eager"
-    if not args.no_graph:
+    # ---------------- pass 1: the timed region: exactly `steps` eager steps ----------------
+    us_per_step = time_loop(step, steps, warmup)
+    log("%s: %.2f us/step over %d steps" % (w.name, us_per_step, steps))
+    res = {"us_per_step": us_per_step, "timed_steps": steps, "buffer_sets": R, "model": model,
+           "graph_us": None, "graph_steps": None, "graph_ok": None, "step_pct": None, "copy_gbps": None,
+           "dense_baseline": None, "recall": None, "cpu": None}
+
+    if full and not args.no_graph:
+        # the same steps as ONE captured graph (one step per buffer set), replayed; every replay is checked
+        ref_T = np.sort(sets[0]["T"].cpu().numpy(), -1)
+        ref_O = sets[0]["O"].cpu().numpy().copy()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -635,17 +750,18 @@ def main():
             for s in sets:
                 step(s)
         torch.cuda.synchronize()
-        for _ in range(max(1, args.warmup // R)):
+        n_replays = max(1, steps // R)
+        for _ in range(max(1, warmup // R)):
             g.replay()
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
-        for _ in range(K_steps // R):
+        for _ in range(n_replays):
             g.replay()
         b.record()
         torch.cuda.synchronize()
-        graph_us = a.elapsed_time(b) / K_steps * 1e3
-        # every replay must reproduce the eager result (same set; output within accumulation-order noise)
+        res["graph_us"] = round(a.elapsed_time(b) / (n_replays * R) * 1e3, 3)
+        res["graph_steps"] = n_replays * R
         ok = True
         for _ in range(3):
             g.replay()
@@ -653,52 +769,54 @@ def main():
             ok &= bool(np.array_equal(np.sort(sets[0]["T"].cpu().numpy(), -1), ref_T))
             ok &= bool(np.abs(sets[0]["O"].cpu().numpy() - ref_O).max() <= 2e-5)
             step(sets[1]); torch.cuda.synchronize()
-        log("graph: %.2f us/step, replays match eager: %s" % (graph_us, ok))
-        if ok and graph_us < eager_us:
-            mode = "hipgraph"
-    us_per_step = graph_us if mode == "hipgraph" else eager_us
+        res["graph_ok"] = ok
+        log("graph: %.2f us/step, replays match eager: %s" % (res["graph_us"], ok))
 
-    # ---------------- pass 1b: distribution of single steps (one event pair per step) ----------------
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K_steps)]
-    for i in range(K_steps):
-        evs[i][0].record(); step(sets[i % R]); evs[i][1].record()
-    torch.cuda.synchronize()
-    per = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
-    step_pct = {"p10": round(float(np.percentile(per, 10)), 3), "p50": round(float(np.percentile(per, 50)), 3),
-                "p90": round(float(np.percentile(per, 90)), 3)}
+    if full:
+        # ---------------- distribution of single steps (one event pair per step: adds ~2 us each) ----------------
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for i in range(steps):
+            evs[i][0].record(); step(sets[i % R]); evs[i][1].record()
+        torch.cuda.synchronize()
+        per = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
+        res["step_pct"] = {"p10": round(float(np.percentile(per, 10)), 3), "p50": round(float(np.percentile(per, 50)), 3),
+                           "p90": round(float(np.percentile(per, 90)), 3), "includes_event_overhead": True}
+        # ---------------- measured ceiling: a plain device copy (read + write bytes per second) ----------------
+        cp_src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda")
+        cp_dst = torch.empty_like(cp_src)
+        for _ in range(3):
+            cp_dst.copy_(cp_src)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            cp_dst.copy_(cp_src)
+        b.record()
+        torch.cuda.synchronize()
+        res["copy_gbps"] = round(2 * cp_src.numel() * 10 / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
+        del cp_src, cp_dst
 
-    # ---------------- measured ceiling: a plain device copy (read + write bytes per second) ----------------
-    cp_src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda")
-    cp_dst = torch.empty_like(cp_src)
-    for _ in range(3):
-        cp_dst.copy_(cp_src)
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(10):
-        cp_dst.copy_(cp_src)
-    b.record()
-    torch.cuda.synchronize()
-    copy_gbps = 2 * cp_src.numel() * 10 / (a.elapsed_time(b) * 1e-3) / 1e9
-    del cp_src, cp_dst
-
-    # ---------------- pass 2: per-kernel GPU time ----------------
+    # ---------------- pass 2: per-kernel GPU time (start/stop timestamps of every launch) ----------------
     fb.fasa_profile_reset()
     fb.fasa_profile_enable(True)
-    for i in range(K_steps):
+    for i in range(steps):
         step(sets[i % R])
     prof = fb.profile_summary()
-    fb.fasa_profile_reset()
-    for i in range(K_steps):
-        dense(sets[i % R])
-    prof_dense = fb.profile_summary()
+    prof_dense = {}
+    if full:
+        fb.fasa_profile_reset()
+        for i in range(steps):
+            dense(sets[i % R])
+        prof_dense = fb.profile_summary()
     fb.fasa_profile_enable(False)
     fb.fasa_profile_reset()
 
-    e = w.elem_bytes
     alg_bytes = {   # algorithmic bytes per launch of each kernel (what the method itself must move)
         "fasa_score_hist": rows * w.n_ctx * 2 * w.n_fc * e,
+        "fasa_score": rows * w.n_ctx * 2 * w.n_fc * e,
         "fasa_select": rows * w.n_ctx * 4,
+        "fasa_select_all": rows * bsel * 4,
         "fasa_sparse_attend": rows * 2 * bsel * w.head_dim * e,
+        "fasa_select_attend": rows * w.n_ctx * 4 + rows * 2 * bsel * w.head_dim * e,    # scores read + rows gathered
         "fasa_dense_attend": rows * 2 * w.n_ctx * w.head_dim * e,
     }
     kernels = {}
@@ -708,26 +826,33 @@ def main():
         if name in alg_bytes:
             ent["alg_bytes"] = alg_bytes[name]
             ent["gbps"] = round(alg_bytes[name] / us / 1e3, 1)
-            ent["traffic"] = MEASURED_TRAFFIC.get((w.config_id, name))
+            ent["traffic"] = measured_traffic(w.config_id, name)
         kernels[name] = ent
-    path_kernels = [k for k in prof if k in alg_bytes]
-    dom = max(path_kernels, key=lambda k: alg_bytes[k])      # the kernel that moves the most bytes
+    # the dominant kernel of the step is the one that takes the longest
+    dom = max(prof, key=lambda k: prof[k][1] / prof[k][0])
     dom_us = prof[dom][1] / prof[dom][0] * 1e3
     achieved = alg_bytes[dom] / dom_us / 1e3
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": MEASURED_TRAFFIC.get((w.config_id, dom))}
-    sum_kernel_us = sum(prof[k][1] / prof[k][0] * 1e3 for k in prof)
+    res["roofline"] = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                       "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "avg_us": round(dom_us, 3),
+                       "alg_bytes": alg_bytes[dom], "traffic": measured_traffic(w.config_id, dom)}
+    res["kernels"] = kernels
+    res["sum_kernel_us"] = sum(prof[k][1] / prof[k][0] * 1e3 for k in prof)
+    if not full:
+        del sets, q0, K0, V0
+        torch.cuda.empty_cache()
+        return res
 
-    dense_us = time_loop(dense, K_steps, args.warmup)
+    dense_us = time_loop(dense, steps, warmup)
     dense_kernel_us = sum(ms / n * 1e3 for n, ms in prof_dense.values())
     log("dense full-KV decode: %.2f us/step" % dense_us)
+    res["dense_baseline"] = {"us_per_step": round(dense_us, 3), "kernel_us": round(dense_kernel_us, 3),
+                             "bytes": model["dense"], "gbps": round(model["dense"] / dense_us / 1e3, 1),
+                             "speedup_of_fasa": round(dense_us / us_per_step, 3)}
 
     # ---------------- selection quality against full-head scores (not timed) ----------------
     # The paper's "Oracle" upper bound ranks tokens by the full-head logits (all d/2 FCs); the share of
     # its top-B set that the F dominant FCs recover is the synthetic analogue of the paper's contextual
     # agreement.  Same kernels, F = d/2.
-    recall = None
     if w.n_fc < w.head_dim // 2 and bsel < w.n_ctx:
         half = w.head_dim // 2
         s0 = sets[0]
@@ -745,12 +870,11 @@ def main():
         step(s0)
         torch.cuda.synchronize()
         Ta, Tf = T_all.cpu().numpy().reshape(rows, -1), s0["T"].cpu().numpy().reshape(rows, -1)
-        recall = float(np.mean([len(np.intersect1d(Ta[r], Tf[r])) / bsel for r in range(rows)]))
+        res["recall"] = round(float(np.mean([len(np.intersect1d(Ta[r], Tf[r])) / bsel for r in range(rows)])), 4)
         del Kp_all, S_all, T_all
-        log("top-B recall of the F=%d dominant FCs against full-head scores: %.4f" % (w.n_fc, recall))
+        log("top-B recall of the F=%d dominant FCs against full-head scores: %.4f" % (w.n_fc, res["recall"]))
 
     # ---------------- pass 3: CPU oracle on the host cores ----------------
-    cpu = None
     if not args.no_cpu_baseline:
         from oracle import fasa_oracle as O
         sub = list(range(w.batch)) if w.batch <= 2 else [0]          # bounded sample of the batch
@@ -763,44 +887,14 @@ def main():
                 break
         wall, cpu_t = time.time() - t_cpu0, time.process_time() - c0
         per_step = wall / reps * (w.batch / len(sub))
-        cpu = {"value": round(per_step * 1e6, 1), "unit": "us", "cores": max(1, int(round(cpu_t / wall))),
-               "kind": "oracle",
-               "sample": "%d full oracle decode steps on %d of %d batch entries, scaled to the batch; "
-                         "numpy float64" % (reps, len(sub), w.batch)}
-        log("cpu oracle: %.0f us/step (%d reps)" % (cpu["value"], reps))
-
-    out = {
-        "metric": "us_per_decode_step", "value": round(us_per_step, 3), "unit": "us",
-        "n_gpus": 1, "steps": K_steps, "warmup": args.warmup, "ms_per_step": round(us_per_step / 1e3, 6),
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
-                   "head_dim": w.head_dim, "n_ctx": w.n_ctx, "budget": bsel, "n_fc": w.n_fc,
-                   "storage_dtype": w.dtype, "pairing": args.pairing, "buffer_sets": R, "launch": mode},
-        "hbm": {"alg_bytes": model["alg"], "alg_plus_intermediate_bytes": model["alg_plus_intermediates"],
-                "step_gbps": round(model["alg"] / us_per_step / 1e3, 1),
-                "step_frac_of_peak": round(model["alg"] / us_per_step / 1e3 / HBM_PEAK_GBPS, 4),
-                # the same with the intermediates (S written and re-read, T) counted: the bytes actually touched
-                "step_touched_gbps": round(model["alg_plus_intermediates"] / us_per_step / 1e3, 1),
-                "step_touched_frac_of_peak": round(model["alg_plus_intermediates"] / us_per_step / 1e3 / HBM_PEAK_GBPS, 4),
-                "kernel_time_gbps": round(model["alg"] / sum_kernel_us / 1e3, 1),
-                "kernel_time_frac_of_peak": round(model["alg"] / sum_kernel_us / 1e3 / HBM_PEAK_GBPS, 4),
-                # second denominator: what a plain 256 MiB device copy moves (read + write) on this machine
-                "copy_ceiling_gbps": round(copy_gbps, 1),
-                "dominant_kernel_frac_of_copy_ceiling": round(achieved / copy_gbps, 4)},
-        "step_us_percentiles": step_pct,
-        "eager_us_per_step": round(eager_us, 3),
-        "graph_us_per_step": None if graph_us is None else round(graph_us, 3),
-        "sum_kernel_us": round(sum_kernel_us, 3),
-        "roofline": roofline,
-        "kernels": kernels,
-        "dense_baseline": {"us_per_step": round(dense_us, 3), "kernel_us": round(dense_kernel_us, 3),
-                           "bytes": model["dense"], "gbps": round(model["dense"] / dense_us / 1e3, 1),
-                           "speedup_of_fasa": round(dense_us / us_per_step, 3)},
-        "selection_recall_vs_full_head": None if recall is None else round(recall, 4),
-        "cpu_baseline": cpu,
-    }
-    print(json.dumps(out), flush=True)
+        res["cpu"] = {"value": round(per_step * 1e6, 1), "unit": "us", "cores": max(1, int(round(cpu_t / wall))),
+                      "kind": "oracle",
+                      "sample": "%d full oracle decode steps on %d of %d batch entries, scaled to the batch; "
+                                "numpy float64" % (reps, len(sub), w.batch)}
+        log("cpu oracle: %.0f us/step (%d reps)" % (res["cpu"]["value"], reps))
+    del sets, q0, K0, V0
+    torch.cuda.empty_cache()
+    return res
 
 
 if __name__ == "__main__":

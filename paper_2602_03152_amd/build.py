@@ -4,6 +4,14 @@
 
 Objects go to paper_2602_03152_amd/_build/, the library to paper_2602_03152_amd/libfasa.so.
 
+    python -m paper_2602_03152_amd.build --sanitize
+
+compiles the same sources with AddressSanitizer and UndefinedBehaviorSanitizer on the HOST side (the
+device code is untouched) into paper_2602_03152_amd/fasa_abi_host_check, a stand-alone program
+(csrc/abi_host_check.cpp) that walks the argument validation of every entry point and the pure host
+functions (workspace sizes, launch plans, list checker) without a GPU, and runs it: any sanitizer
+report fails the build (tests/test_host_sanitizers.py does the same).
+
     python -m paper_2602_03152_amd.build --trace
 
 builds a second library, paper_2602_03152_amd/libfasa_trace.so, with device-side stage timers compiled
@@ -175,6 +183,36 @@ def _check_asm(source, extra_flags, bdir, verbose):
         raise RuntimeError("%s: registers of uncounted loads are touched before their wait: %s" % (source, bad[:5]))
 
 
+HOST_CHECK = os.path.join(PKG, "fasa_abi_host_check")
+SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+            "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def build_sanitized(verbose: bool = True, run: bool = True) -> str:
+    """Host-sanitized build of the library's sources into the ABI exerciser; runs it unless run=False.
+    Raises on a compile error, a failed check or a sanitizer report."""
+    bdir = os.path.join(BUILD, "sanitize")
+    os.makedirs(bdir, exist_ok=True)
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1"] + SANITIZE
+    objs = [os.path.join(bdir, s.replace(".hip", ".o")) for s in SOURCES]
+    cmds = [[HIPCC, *flags, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    main_o = os.path.join(bdir, "abi_host_check.o")
+    cmds.append([HIPCC, *flags, "-x", "hip", "-c", os.path.join(CSRC, "abi_host_check.cpp"), "-o", main_o])
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        for fut in [ex.submit(_run, c, verbose) for c in cmds]:
+            fut.result()
+    _run([HIPCC, "--offload-arch=gfx950", *SANITIZE, "-o", HOST_CHECK, main_o, *objs], verbose)
+    if run:
+        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0:exitcode=23",
+                   UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+        p = subprocess.run([HOST_CHECK], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env)
+        if verbose:
+            print(p.stdout, flush=True)
+        if p.returncode != 0 or "all checks passed" not in p.stdout or "runtime error" in p.stdout or "ERROR: AddressSanitizer" in p.stdout:
+            raise RuntimeError("sanitized ABI check failed (exit %d):\n%s" % (p.returncode, p.stdout[-4000:]))
+    return HOST_CHECK
+
+
 def build(verbose: bool = True, extra_flags=(), trace: bool = False) -> str:
     lib, bdir = LIB, BUILD
     if trace:
@@ -195,4 +233,7 @@ def build(verbose: bool = True, extra_flags=(), trace: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print("built", build(verbose="-q" not in sys.argv, trace="--trace" in sys.argv))
+    if "--sanitize" in sys.argv:
+        print("built and ran", build_sanitized(verbose="-q" not in sys.argv))
+    else:
+        print("built", build(verbose="-q" not in sys.argv, trace="--trace" in sys.argv))

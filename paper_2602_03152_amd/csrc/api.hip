@@ -62,11 +62,11 @@ static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 AttendPlan plan_attend(int rows, int count, int group) {
   // The attention kernels are gather-bound and all their workgroups should be resident at once:
-  // a second, partly filled round of workgroups costs as much as a full one.  MI355X has 256 CUs;
-  // two workgroups (8 waves) per CU measured best for every workload shape and GQA group (more
-  // splits only add partial results to publish and merge).
+  // a second, partly filled round of workgroups costs as much as a full one.  Two workgroups (8 waves)
+  // per CU measured best for every workload shape and GQA group (more splits only add partial results
+  // to publish and merge).
   (void)group;
-  const long long slots = 256LL * 2;
+  const long long slots = 2LL * kAssumedCUs;
   const long long total = (long long)rows * count;
   const long long by_size = (total + 63) / 64;           // workgroups of at least 64 list entries
   long long nblocks;

@@ -3,7 +3,7 @@
 // K/V rows it names, keeps a running (max, sum, weighted V) per query head of the GQA group, and
 // the workgroup that finishes a row last merges the row's chunks.  The same kernel with the index list replaced by the
 // identity is the full-KV baseline (paper Sec. 4.4).
-#include "attend_common.h"
+#include "mfma_tile.h"
 
 namespace fasa {
 
@@ -216,17 +216,14 @@ __global__ __launch_bounds__(256) void attend_kernel(const ET* __restrict__ q,
 }
 
 // ---------------------------------------------------------------------------------------------
-// bf16 variant with the logits on the matrix cores.  For a GQA group the logits of 16 gathered
-// rows are the 16x16 product K_tile (16 rows x 128 dims) . Q^T (128 dims x G, padded to 16): four
-// v_mfma_f32_16x16x32_bf16, whose A operand wants exactly one 16-byte chunk of a K row per lane.
-// That removes the per-row cross-lane reductions and the G-fold multiply-adds of the vector
-// version; the weighted sum of V stays on the vector ALUs (a row-major V row cannot be fed to an
-// MFMA operand without a transpose), with the weights handed over through LDS.
-//   K tile, lane (tok = lane & 15, j = lane >> 4): chunks j, j+4, j+8, j+12 of row tok
-//   logits C, lane (g = lane & 15, j): rows 4j..4j+3 of the tile for query head g
-//   V tile, lane (r = lane >> 4, c = lane & 15): head dims 8c..8c+7 of rows r, r+4, r+8, r+12
+// bf16 variant with both products of a 16-row tile on the matrix cores (mfma_tile.h): the logits
+// K_tile . Q^T of the GQA group and the weighted sum P . V_tile.  The tile loop is software-pipelined:
+// while a tile is computed, the next tile's K/V rows and the list entries of the tile after it are in
+// flight.  Loads inside the loop are unconditional (straight-line code keeps the compiler's wait
+// counts exact: a test around a load would turn every later wait into a wait for everything);
+// entries beyond the range are clamped into it and only fetched, the K/V prefetch is issued for real
+// tiles only (the last tile is peeled).
 // ---------------------------------------------------------------------------------------------
-
 template <int G, bool DENSE>
 __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __restrict__ q,
                                                           const uint16_t* __restrict__ K,
@@ -244,13 +241,16 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
                                                           const int32_t* __restrict__ budget_seq,
                                                           PageMap pm) {
   constexpr int D = kHeadDim;
+  // the waves' totals, later the merge's partition scratch (< 8 KB) and, behind it, its split weights
+  constexpr int ACC_BYTES = 4 * G * D * 4;
+  constexpr int MERGE_BYTES = 8192 + G * kMaxSplitsLds * 4;
+  __shared__ __align__(16) unsigned char big[ACC_BYTES > MERGE_BYTES ? ACC_BYTES : MERGE_BYTES];
   __shared__ float sm_m[4][G], sm_l[4][G];
-  __shared__ __align__(16) float sm_acc[4][4][G][D];   // [wave][16-lane group]: weighted V over the group's rows
-  __shared__ float wsm[G * kMaxSplitsLds];
   __shared__ float red[G];
   __shared__ uint32_t ticket;
-  __shared__ __align__(16) float pt[4][16][8];   // per wave: weights of the tile, [row][query head]
-  __shared__ __align__(16) float scs[4][8];      // per wave: rescale factor of the running sums
+  __shared__ __align__(16) float scs[4][16];      // per wave: rescale factor of each head's running sums
+  float (*sm_o)[G][D] = reinterpret_cast<float (*)[G][D]>(big);
+  float* wsm = reinterpret_cast<float*>(big + 8192);
 
   int row, split;
   row_slice_of_block(rows, n_splits, row, split);
@@ -267,20 +267,9 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
   FASA_T_DECL(5);
   FASA_T(0);
 
-  // B operands: Q^T, column g = lo (zero beyond G), k-slots (hi, 0..7) of MFMA i = dims 8(hi+4i)..+7
-  bf16x8_t qb[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (lo < G) v = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + (size_t)h * G + lo) * D + 8 * (hi + 4 * i));
-    qb[i] = __builtin_bit_cast(bf16x8_t, v);
-  }
-  float acc[G][8];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int k = 0; k < 8; ++k) acc[g][k] = 0.f;
-  float m_run = kNegBig, l_run = 0.f;   // of query head lo, over this lane's rows of every tile
+  MfmaTile<G> tile;
+  tile.load_q(q + ((size_t)b * Hq + (size_t)h * G) * D, lo, hi);
+  tile.reset();
 
   // list entries are token numbers, or pool slots of a paged cache (block << shift | offset)
   const bool paged = pm.table != nullptr;
@@ -291,28 +280,21 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
   const uint16_t* Vb = V + (paged ? 0 : b * sb) + h * sh + 8 * lo;
   const int32_t* Trow = DENSE ? nullptr : T + (size_t)row * count_max;
 
-  // ---- tile loop, software-pipelined: while a tile is computed, the next tile's K/V rows and the
-  // indices of the tile after it are in flight.  The loads inside the loop are unconditional
-  // (straight-line code keeps the compiler's wait counts exact: a test around a load would turn
-  // every later wait into a wait for everything); indices beyond the range are clamped into it and
-  // only fetched, the K/V prefetch is issued for real tiles only (the last tile is peeled). ----
-  struct TileIdx { int k; int v[4]; };        // list entries (token numbers) of one tile
-  struct TileKV { uint4 kc[4], vc[4]; };
+  struct TileIdx { int k; int v[4]; };        // list entries of one tile: K row lo, V rows 4hi .. 4hi+3
   auto load_idx = [&](int j0) {
     TileIdx r;
     if constexpr (DENSE) {
       r.k = min(j0 + lo, s1 - 1);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) r.v[u] = min(j0 + 4 * u + hi, s1 - 1);
+      for (int i = 0; i < 4; ++i) r.v[i] = min(j0 + 4 * hi + i, s1 - 1);
     } else {
       // a stray index can never become a stray address: entries are clamped to the cache below
       r.k = Trow[min(j0 + lo, s1 - 1)];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) r.v[u] = Trow[min(j0 + 4 * u + hi, s1 - 1)];
+      for (int i = 0; i < 4; ++i) r.v[i] = Trow[min(j0 + 4 * hi + i, s1 - 1)];
     }
     return r;
   };
-  // gather: one K row per lane column (chunks hi, hi+4, hi+8, hi+12), four V rows per lane group
   auto load_kv = [&](const TileIdx& ix) {
     TileKV r;
     auto row_off = [&](int e) {
@@ -323,84 +305,16 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
 #pragma unroll
     for (int i = 0; i < 4; ++i) r.kc[i] = *reinterpret_cast<const uint4*>(Kb + koff + 8 * (hi + 4 * i));
 #pragma unroll
-    for (int u = 0; u < 4; ++u) r.vc[u] = *reinterpret_cast<const uint4*>(Vb + row_off(ix.v[u]));
+    for (int i = 0; i < 4; ++i) r.vr[i] = *reinterpret_cast<const uint4*>(Vb + row_off(ix.v[i]));
     return r;
   };
   auto compute_tile = [&](const TileKV& kv, int j0) {
-    // The scaled logit is rounded once and that rounded value is what the running maximum and the
-    // exponent see: the scaling is never fused into the subtraction of the maximum (the weight of
-    // the maximal row must be exactly 1).  Explicit fmaf calls below are not affected.
-#pragma clang fp contract(off)
-    // ---- logits of the tile: rows 4hi..4hi+3, query head lo ----
-    f32x4_t c = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kv.kc[i]), qb[i], c, 0, 0, 0);
-
     float sv[4];
+    tile.logits(kv, scale_log2e, sv);
     bool valid[4];
-    float mx = kNegBig;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      valid[e] = j0 + 4 * hi + e < s1;
-      sv[e] = c[e] * scale_log2e;
-      mx = valid[e] ? fmaxf(mx, sv[e]) : mx;
-    }
-    mx = xor32_max(xor16_max(mx));
-    const float m_new = fmaxf(m_run, mx);
-    const float sc = exp2f(m_run - m_new);
-    m_run = m_new;
-    float psum = 0.f;
-    float pv[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      pv[e] = valid[e] ? exp2f(sv[e] - m_new) : 0.f;
-      psum += pv[e];
-    }
-    l_run = fmaf(l_run, sc, psum);
-    if (lo < 8) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) pt[wave][4 * hi + e][lo] = pv[e];
-      if (hi == 0) scs[wave][lo] = sc;
-    }
-    // same wave writes and reads: LDS operations of a wave complete in order; the fence only keeps
-    // the compiler from moving the reads above the writes
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    // ---- weighted sum of V on the vector ALUs ----
-    float scg[8];
-    {
-      const float4 a0 = *reinterpret_cast<const float4*>(&scs[wave][0]);
-      const float4 a1 = *reinterpret_cast<const float4*>(&scs[wave][4]);
-      scg[0] = a0.x; scg[1] = a0.y; scg[2] = a0.z; scg[3] = a0.w;
-      scg[4] = a1.x; scg[5] = a1.y; scg[6] = a1.z; scg[7] = a1.w;
-    }
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int k = 0; k < 8; ++k) acc[g][k] *= scg[g];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      float pg[8];
-      const float4 p0 = *reinterpret_cast<const float4*>(&pt[wave][4 * u + hi][0]);
-      pg[0] = p0.x; pg[1] = p0.y; pg[2] = p0.z; pg[3] = p0.w;
-      if (G > 4) {
-        const float4 p1 = *reinterpret_cast<const float4*>(&pt[wave][4 * u + hi][4]);
-        pg[4] = p1.x; pg[5] = p1.y; pg[6] = p1.z; pg[7] = p1.w;
-      }
-      float vf[8];
-      const uint4 vw = kv.vc[u];
-      vf[0] = bf16_lo(vw.x); vf[1] = bf16_hi(vw.x); vf[2] = bf16_lo(vw.y); vf[3] = bf16_hi(vw.y);
-      vf[4] = bf16_lo(vw.z); vf[5] = bf16_hi(vw.z); vf[6] = bf16_lo(vw.w); vf[7] = bf16_hi(vw.w);
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int k = 0; k < 8; ++k) acc[g][k] = fmaf(pg[g], vf[k], acc[g][k]);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();   // the tile's weights are consumed before the next tile overwrites them
+    for (int e = 0; e < 4; ++e) valid[e] = j0 + 4 * hi + e < s1;
+    tile.accumulate(kv, sv, valid, &scs[wave][0], lo, hi);
   };
 
   const int jw = s0 + wave * 16;               // this wave's tiles start at jw, jw + 64, ...
@@ -417,44 +331,17 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
     }
     compute_tile(cur, jw + 64 * (n_tiles - 1));
   }
-
   FASA_T(1);
-  // ---- workgroup totals.  The four 16-lane groups of a wave hold weighted V sums over different
-  // rows at one common scale (the running maximum is per head, not per group): they go to LDS as
-  // they are, 16 partial sums per output, and the merge below adds them - far fewer instructions
-  // than butterflies over 8 G registers per lane. ----
-  l_run = xor32_sum(xor16_sum(l_run));
-  if (hi == 0 && lo < G) { sm_m[wave][lo] = m_run; sm_l[wave][lo] = l_run; }
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float4* dst = reinterpret_cast<float4*>(&sm_acc[wave][hi][g][8 * lo]);
-    dst[0] = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
-    dst[1] = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
-  }
+  tile.finish(&sm_m[wave][0], &sm_l[wave][0], &sm_o[wave][0][0], lo, hi);
   __syncthreads();
 
-  // merge: thread (query head g, 4 head dims)
+  // workgroup totals: thread (query head g, 4 head dims)
   const size_t pbase = ((size_t)row * n_splits + split) * G;
   if (t < G * (D / 4)) {
     const int g = t / (D / 4), d4 = t % (D / 4);
-    float mn = sm_m[0][g];
-#pragma unroll
-    for (int w = 1; w < 4; ++w) mn = fmaxf(mn, sm_m[w][g]);
-    float ls = 0.f;
-    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float sc = exp2f(sm_m[w][g] - mn);
-      ls = fmaf(sm_l[w][g], sc, ls);
-      float4 sw = *reinterpret_cast<const float4*>(&sm_acc[w][0][g][4 * d4]);
-#pragma unroll
-      for (int r = 1; r < 4; ++r) {
-        const float4 x = *reinterpret_cast<const float4*>(&sm_acc[w][r][g][4 * d4]);
-        sw.x += x.x; sw.y += x.y; sw.z += x.z; sw.w += x.w;
-      }
-      a.x = fmaf(sw.x, sc, a.x); a.y = fmaf(sw.y, sc, a.y);
-      a.z = fmaf(sw.z, sc, a.z); a.w = fmaf(sw.w, sc, a.w);
-    }
+    float mn, ls;
+    float4 a;
+    tile_wg_totals<G>(&sm_m[0][0], &sm_l[0][0], &sm_o[0][0][0], g, d4, mn, ls, a);
     if (n_splits == 1) {
       *reinterpret_cast<float4*>(O + ((size_t)b * Hq + (size_t)h * G + g) * D + 4 * d4) =
           make_float4(a.x / ls, a.y / ls, a.z / ls, a.w / ls);
@@ -475,7 +362,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(const uint16_t* __rest
                FASA_T_D(1, 0), FASA_T_D(2, 1), FASA_T_D(3, 2));
   if (ticket != (uint32_t)n_splits - 1u) return;
   if (t == 0) ctl[row].done_att = 0;
-  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, n_splits, wsm, red, &sm_acc[0][0][0][0]);
+  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, n_splits, n_splits, wsm, red, reinterpret_cast<float*>(big));
   FASA_T(4);
   FASA_T_PRINT(t == 0 && row == 0, "attend last(row0, split %d): tiles %llu merge %llu publish+ticket %llu combine %llu (x10ns)\n",
                split, FASA_T_D(1, 0), FASA_T_D(2, 1), FASA_T_D(3, 2), FASA_T_D(4, 3));

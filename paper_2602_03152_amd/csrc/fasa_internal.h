@@ -21,6 +21,9 @@ constexpr int kHistBins = 1 << kHistBits;  // (sign, 8 exponent bits, 3 mantissa
 constexpr int kKeyLowBits = 32 - kHistBits;
 constexpr int kHeadDim = 128;
 constexpr int kMaxGroup = 8;
+// Compute units the launch plans are sized for (MI355X).  A compile-time number because
+// fasa_workspace_bytes() has to be a pure host function; a GPU test checks it against the device.
+constexpr int kAssumedCUs = 256;
 
 // Per-(b,h) row counters, one 128-byte line per row so that rows served by different XCDs never
 // share a line.  All zero between calls: the workgroup that finishes a row resets what it used.

@@ -24,9 +24,7 @@
 //        into one more partial.  Rows with more candidates (degenerate score distributions) resolve by
 //        counting or by the radix resolve and gather the taken rows themselves;
 //     6. merges all partials into O and leaves histogram and counters zeroed for the next call.
-#include <cstdlib>
-
-#include "attend_common.h"
+#include "mfma_tile.h"
 #include "select_common.h"
 
 namespace fasa {
@@ -128,14 +126,8 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   uint32_t* gh = hist + (size_t)row * kHistBins;
   const uint4 h4 = *reinterpret_cast<const uint4*>(gh + 4 * t);
   const float bin_mu = ctl[row].bin_mu, bin_inv = ctl[row].bin_inv;
-  // B operands: Q^T, column g = lo (zero beyond G), k-slots (hi, 0..7) of MFMA i = dims 8(hi+4i)..+7
-  bf16x8_t qb[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint4 x = make_uint4(0, 0, 0, 0);
-    if (lo < G) x = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + (size_t)h * G + lo) * D + 8 * (hi + 4 * i));
-    qb[i] = __builtin_bit_cast(bf16x8_t, x);
-  }
+  MfmaTile<G> tile;
+  tile.load_q(q + ((size_t)b * Hq + (size_t)h * G) * D, lo, hi);
   const bool paged = pm.table != nullptr;
   int slot[PT];
   if (paged) {
@@ -167,11 +159,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   uint32_t pw, pc, tw, tc;
   block256_prefix2(__popc(win), __popc(cnd), wtot, pw, pc, tw, tc);
   const int n_win = (int)min(tw, (uint32_t)TPB);
-#ifdef FASA_NO_RICH
-  const bool rich = false;
-#else
   const bool rich = thr[2] <= (uint32_t)kFuseRich;      // the same decision in every workgroup of the row
-#endif
   const int n_ride = rich ? (int)min(min(tc, (uint32_t)kStashRecs), (uint32_t)(TPB - n_win)) : 0;
   const bool overflow = rich && tc > (uint32_t)n_ride;   // then the row's last workgroup gathers the taken rows itself
   const int n_list = n_win + n_ride;
@@ -197,21 +185,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   const uint16_t* Kb = K + (paged ? 0 : b * sb) + h * sh;
   const uint16_t* Vb = V + (paged ? 0 : b * sb) + h * sh + 8 * lo;
 
-  // One tile = 16 list entries.  Both products of a tile run on the matrix cores:
-  //   logits  C[row][head] = K_tile (16 rows x 128 dims) . Q^T: four v_mfma_f32_16x16x32_bf16; lane
-  //           (lo, hi) supplies chunks hi, hi+4, hi+8, hi+12 of K row lo and receives the logits of rows
-  //           4hi .. 4hi+3 for query head lo;
-  //   output  O[head][dim] += P (16 heads x 16 rows) . V_tile (16 rows x 128 dims): the lane's four
-  //           weights are already where the A operand wants them (head lo, rows 4hi .. 4hi+3).  The B
-  //           operand wants, per lane, the same four rows at ONE head dim: lane (lo, hi) loads 16 bytes
-  //           (dims 8lo .. 8lo+7) of V rows 4hi .. 4hi+3, and MFMA j of eight takes dim 8lo + j of each,
-  //           two byte permutes per MFMA.  Its result column lo is head dim 8lo + j, rows 4hi .. 4hi+3
-  //           are query heads 4hi .. 4hi+3.
-  // The weights are float32 numbers in [0, 1]; the matrix cores take bf16.  Each weight goes in as
-  // hi + lo, hi = its top 16 bits, lo = the top 16 bits of the exact remainder: k-slots 0-3 of the
-  // 32-deep MFMA carry hi, slots 4-7 lo, against the same four V values twice.  What is dropped is
-  // below 2^-16 of the weight; V is bf16 already, the products are exact, the sums float32.
-  struct TileKV { uint4 kc[4], vr[4]; };
+  // One tile = 16 list entries, both products on the matrix cores (mfma_tile.h).
   auto row_off = [&](int e) {
     const int sl = min(max(e, 0), slot_max);   // a stray entry can never become a stray address
     return (long long)(sl >> pshift) * blk_stride + (long long)(sl & pmask) * sn;
@@ -229,29 +203,14 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     for (int i = 0; i < 4; ++i) r.vr[i] = *reinterpret_cast<const uint4*>(Vb + voff[i]);
     return r;
   };
-  f32x4_t oc[8];            // oc[j][e]: weighted V of query head 4hi + e at head dim 8lo + j
-  float m_run, l_run;       // of query head lo; l_run over this lane's rows only until the end
   // rows j0 .. j0+15 of a list whose first nw entries are attended and whose entries nw .. cnt-1 are
   // candidates: those only leave their logits and V row in the stash, entry (entry - nw)
   auto compute_tile = [&](const TileKV& kv, int j0, int nw, int cnt) {
-    // The scaled logit is rounded once and that rounded value is what the running maximum and the
-    // exponent see: the scaling is never fused into the subtraction of the maximum (the weight of
-    // the maximal row must be exactly 1).  Explicit fmaf calls below are not affected.
-#pragma clang fp contract(off)
-    f32x4_t c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};   // two chains of two: half the latency
-    c0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kv.kc[0]), qb[0], c0, 0, 0, 0);
-    c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kv.kc[1]), qb[1], c1, 0, 0, 0);
-    c0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kv.kc[2]), qb[2], c0, 0, 0, 0);
-    c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kv.kc[3]), qb[3], c1, 0, 0, 0);
     float sv[4];
+    tile.logits(kv, scale_log2e, sv);
     bool valid[4];
-    float mx = kNegBig;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      valid[e] = j0 + 4 * hi + e < nw;
-      sv[e] = (c0[e] + c1[e]) * scale_log2e;
-      mx = valid[e] ? fmaxf(mx, sv[e]) : mx;
-    }
+    for (int e = 0; e < 4; ++e) valid[e] = j0 + 4 * hi + e < nw;
     if (j0 + 16 > nw && cnt > nw) {   // (wave-uniform) this tile holds candidates
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -262,47 +221,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
         }
       }
     }
-    mx = xor32_max(xor16_max(mx));
-    const float m_new = fmaxf(m_run, mx);
-    const float sc = exp2f(m_run - m_new);
-    m_run = m_new;
-    uint32_t ph[4], pl[4];
-    float psum = 0.f;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float pv = valid[e] ? exp2f(sv[e] - m_new) : 0.f;
-      psum += pv;
-      ph[e] = __float_as_uint(pv) & 0xffff0000u;
-      pl[e] = __float_as_uint(pv - __uint_as_float(ph[e]));      // exact; its own top 16 bits go in
-    }
-    l_run = fmaf(l_run, sc, psum);
-    // A operand: k-slots (hi, 0..3) = hi parts of rows 4hi .. 4hi+3, (hi, 4..7) = lo parts
-    const uint4 aw = make_uint4(__builtin_amdgcn_perm(ph[1], ph[0], 0x07060302u), __builtin_amdgcn_perm(ph[3], ph[2], 0x07060302u),
-                                __builtin_amdgcn_perm(pl[1], pl[0], 0x07060302u), __builtin_amdgcn_perm(pl[3], pl[2], 0x07060302u));
-    const bf16x8_t pa = __builtin_bit_cast(bf16x8_t, aw);
-    // the rescale factor of head lo has to reach the lanes that hold head lo's sums (heads 4hi .. 4hi+3)
-    if (hi == 0) scs[wave][lo] = sc;
-    // same wave writes and reads: LDS operations of a wave complete in order; the fences only keep the
-    // compiler from moving the accesses across
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const float4 s4 = *reinterpret_cast<const float4*>(&scs[wave][4 * hi]);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();   // read before the next tile overwrites it
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;   // which half of word j / 2
-      const uint32_t w0 = j < 2 ? kv.vr[0].x : j < 4 ? kv.vr[0].y : j < 6 ? kv.vr[0].z : kv.vr[0].w;
-      const uint32_t w1 = j < 2 ? kv.vr[1].x : j < 4 ? kv.vr[1].y : j < 6 ? kv.vr[1].z : kv.vr[1].w;
-      const uint32_t w2 = j < 2 ? kv.vr[2].x : j < 4 ? kv.vr[2].y : j < 6 ? kv.vr[2].z : kv.vr[2].w;
-      const uint32_t w3 = j < 2 ? kv.vr[3].x : j < 4 ? kv.vr[3].y : j < 6 ? kv.vr[3].z : kv.vr[3].w;
-      const uint32_t b01 = __builtin_amdgcn_perm(w1, w0, sel), b23 = __builtin_amdgcn_perm(w3, w2, sel);
-      const bf16x8_t vb = __builtin_bit_cast(bf16x8_t, make_uint4(b01, b23, b01, b23));
-      f32x4_t o = oc[j];
-      o[0] *= s4.x; o[1] *= s4.y; o[2] *= s4.z; o[3] *= s4.w;
-      oc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vb, o, 0, 0, 0);
-    }
+    tile.accumulate(kv, sv, valid, &scs[wave][0], lo, hi);
   };
   // Tiles of 16 entries; wave w takes tiles w, w + 4, ...  While a tile is computed the next one's
   // rows are in flight (loads unconditional, the last tile peeled: exact wait counts).  Ends with the
@@ -311,11 +230,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   // anything waits for it: the place for a memory round trip that nothing else would hide.
   // nw, cnt: see compute_tile.
   auto attend_list = [&](auto&& idx, int nw, int cnt, auto&& under_first_load) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) oc[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    m_run = kNegBig;
-    l_run = 0.f;
-    if (hi == 0) scs[wave][lo] = 1.0f;         // also the heads beyond the group: their lanes see a finite factor
+    tile.reset();
     const int jw = wave * 16;
     if (jw < cnt) {
       const int n_tiles = (cnt - jw + 63) / 64;
@@ -330,34 +245,12 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     } else {
       under_first_load();
     }
-    l_run = xor32_sum(xor16_sum(l_run));
-    if (hi == 0 && lo < G) { sm_m[wave][lo] = m_run; sm_l[wave][lo] = l_run; }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int g = 4 * hi + e;
-      if (g < G) {
-        float4* dst = reinterpret_cast<float4*>(&sm_o[wave][g][8 * lo]);
-        dst[0] = make_float4(oc[0][e], oc[1][e], oc[2][e], oc[3][e]);
-        dst[1] = make_float4(oc[4][e], oc[5][e], oc[6][e], oc[7][e]);
-      }
-    }
+    tile.finish(&sm_m[wave][0], &sm_l[wave][0], &sm_o[wave][0][0], lo, hi);
     __syncthreads();
   };
   // workgroup totals of thread (query head g, 4 head dims), t < 32 G: max, sum, weighted V
   auto wg_totals = [&](int g, int d4, float& mn, float& ls, float4& a) {
-    mn = sm_m[0][g];
-#pragma unroll
-    for (int w = 1; w < 4; ++w) mn = fmaxf(mn, sm_m[w][g]);
-    ls = 0.f;
-    a = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float sc = exp2f(sm_m[w][g] - mn);
-      ls = fmaf(sm_l[w][g], sc, ls);
-      const float4 sw = *reinterpret_cast<const float4*>(&sm_o[w][g][4 * d4]);
-      a.x = fmaf(sw.x, sc, a.x); a.y = fmaf(sw.y, sc, a.y);
-      a.z = fmaf(sw.z, sc, a.z); a.w = fmaf(sw.w, sc, a.w);
-    }
+    tile_wg_totals<G>(&sm_m[0][0], &sm_l[0][0], &sm_o[0][0][0], g, d4, mn, ls, a);
   };
 
   attend_list([&](int j) { return wl[j]; }, n_win, n_list, [&]() {
@@ -591,12 +484,10 @@ FusePlan plan_fused(const fasa_shape& s, bool by_sequence) {
   // once): small problems are latency-bound and gain from short slices with few winners each, large
   // ones from fewer partials to publish and merge and fewer fixed costs per workgroup.  Measured on
   // the five workload shapes: 1024 / 4096 / 2048 / 2048 tokens for shapes 1 - 4.
-  static const int forced = [] { const char* e = getenv("FASA_FUSE_TPB"); return e ? atoi(e) : 0; }();
-  if (forced == 1) return p;
   for (int tpb : {1024, 2048, 4096}) {
     const int ns = (s.n_ctx + tpb - 1) / tpb;
     if (ns > kMaxSplitsLds) continue;
-    if (forced ? tpb == forced : (rows * ns <= 512 || tpb == 4096)) { p.tpb = tpb; p.nslices = ns; return p; }
+    if (rows * ns <= 2 * kAssumedCUs || tpb == 4096) { p.tpb = tpb; p.nslices = ns; return p; }
   }
   return p;                                                  // rows longer than 256 slices of 4096
 }

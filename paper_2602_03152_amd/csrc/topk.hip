@@ -22,7 +22,7 @@ namespace fasa {
 // workgroups per CU (small problems are latency-bound: the shorter slice shortens every workgroup;
 // large ones are throughput-bound: fewer, longer workgroups publish and queue less).
 constexpr int kSelTokLong = 2048, kSelTokShort = 1024;
-constexpr int kSelShortMaxBlocks = 512;
+constexpr int kSelShortMaxBlocks = 2 * kAssumedCUs;
 constexpr int kCandLds = 4096;                  // candidates resolved out of LDS; more: global reads
 
 // 1-D grid of rows * nslices workgroups, nslices = ceil(N / TPB), TPB tokens per workgroup

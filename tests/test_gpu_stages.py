@@ -288,3 +288,14 @@ def test_strided_kv_cache(fb):
     T = np.sort(to_host(d.T), axis=-1)
     ref = O.sparse_attend(x["q"], x["K"], x["V"], T)
     assert np.abs(to_host(d.O) - ref).max() <= OUT_ATOL
+
+
+def test_launch_plans_assume_this_device():
+    """The launch plans and workspace sizes are computed on the host for a fixed number of compute units
+    (fasa_workspace_bytes is a pure function): that number must be the device's."""
+    import os
+    import re
+    src = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2602_03152_amd", "csrc",
+                            "fasa_internal.h")).read()
+    assumed = int(re.search(r"constexpr int kAssumedCUs = (\d+);", src).group(1))
+    assert torch.cuda.get_device_properties(0).multi_processor_count == assumed
