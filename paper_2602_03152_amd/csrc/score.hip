@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
   __shared__ float qsum[256];      // [t]: sum over the group of q[., t mod 128] (upper half: copies)
   __shared__ int32_t fcl[256];     // [t]: dims of list entry min(t, F - 1): lo (PAIRS: lo | hi << 8)
   __shared__ float2 qs[D / 2];
-  __shared__ uint32_t lh[HIST ? NBINS : 1];
+  __shared__ __align__(8) uint32_t lh[HIST ? NBINS : 2];
   __shared__ float2 sst[4];        // adaptive histogram: per wave, sum and sum of squares of its sample scores
   __shared__ ET knew[APPEND ? D : 1];          // the new key row
   __shared__ uint2 kpair[APPEND ? D / 2 : 1];  // per plane: the new key's (lo, hi) as stored in Kp
@@ -306,10 +306,9 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
   if constexpr (HIST == kHistAdaptive) {   // for the selection kernel (stored last: no load waits behind it)
     if (slice == 0 && t == 0) { ctl[row].bin_mu = bin_mu; ctl[row].bin_inv = bin_inv; }
   }
-  if constexpr (HIST != 0) {
+  if constexpr (HIST == kHistKeyBits) {
     __syncthreads();
     // all counters of the thread are read before the first is tested: one LDS round trip, not one each
-    // (a row's histogram region is kHistBins counters whichever binning fills it)
     uint32_t* gh = hist + (size_t)row * kHistBins;
     uint32_t c[NBINS / 256];
 #pragma unroll
@@ -317,6 +316,18 @@ __global__ __launch_bounds__(256) void score_kernel(const ET* __restrict__ q, ET
 #pragma unroll
     for (int k = 0; k < NBINS / 256; ++k)
       if (c[k]) atomicAdd(&gh[t + 256 * k], c[k]);
+  }
+  if constexpr (HIST == kHistAdaptive) {
+    __syncthreads();
+    // Neighbouring bins are flushed as ONE 64-bit add (a 32-bit counter never carries into the next):
+    // the fine bins around the threshold are populated in runs, so this nearly halves the global
+    // atomics, which are what the flush costs.  Thread t: bin pairs t and t + 256 of the row's
+    // kLinBins = 1024 bins (a row's histogram region is kHistBins counters whichever binning fills it).
+    static_assert(kLinBins == 1024, "two bin pairs per thread");
+    unsigned long long* gh = reinterpret_cast<unsigned long long*>(hist + (size_t)row * kHistBins);
+    const uint2 c0 = reinterpret_cast<const uint2*>(lh)[t], c1 = reinterpret_cast<const uint2*>(lh)[t + 256];
+    if (c0.x | c0.y) atomicAdd(&gh[t], (unsigned long long)c0.x | ((unsigned long long)c0.y << 32));
+    if (c1.x | c1.y) atomicAdd(&gh[t + 256], (unsigned long long)c1.x | ((unsigned long long)c1.y << 32));
   }
 }
 
