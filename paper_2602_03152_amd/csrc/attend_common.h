@@ -68,7 +68,7 @@ struct ExtraSplit {
 // memory round trip.  It must leave wsm, red and the extra split's arrays consistent behind a block
 // barrier of its own if it writes them.
 struct NothingUnderLoads { __device__ void operator()() const {} };
-template <int G, typename UnderLoads = NothingUnderLoads>
+template <int G, typename UnderLoads = NothingUnderLoads, int RS = 32 /* splits in flight per thread and round */>
 __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
                                             const float* __restrict__ part_ml,
                                             float* __restrict__ O, int row, int b, int h, int Hq,
@@ -79,7 +79,7 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
   constexpr int D = kHeadDim;
   constexpr int C = G * (D / 4);
   constexpr int P = 256 / C >= 4 ? 4 : (256 / C >= 2 ? 2 : 1);
-  constexpr int RS = 32;                // splits in flight per thread and round
+  static_assert(RS % 8 == 0 && RS >= 8, "whole chunks of eight");
   constexpr int NG = (G + 3) / 4;
   const int t = threadIdx.x;
   const int wave = t >> 6, lane = t & 63;

@@ -6,7 +6,9 @@
 //   launch      an empty kernel, back to back on one stream (eager and as one captured graph)
 //   read        plain streaming reads of 16 MiB and 128 MiB (16-byte loads, 16 per thread in flight)
 //   read+write  1 MiB read, 64 KiB written (the traffic shape of a selection pass)
-//   gather      8 MiB of 256-byte rows at random positions of a 128 MiB cache (K and V of one step)
+//   gather      8 MiB of 256-byte rows at random positions of a 128 MiB cache (K and V of one step of the
+//               Llama-3-8B-shaped workload), and 97 MiB out of 512 MiB (the long-CoT workload: 32 rows x
+//               6193 of 32768 tokens), ascending within a row as the selection leaves them
 //   hand-off    inside one launch: store -> acknowledgement -> ticket atomic -> the last workgroup
 //               reads what the others published (the cost of every "last workgroup merges" phase)
 // Every timed buffer rotates over a pool larger than the last-level cache, so reads come from HBM.
@@ -140,7 +142,7 @@ int main() {
   }
 
   // ---- plain reads ----
-  const size_t pool_bytes = (size_t)1 << 30;     // 1 GiB pool, rotated
+  const size_t pool_bytes = (size_t)2 << 30;     // 2 GiB pool, rotated
   uint4* pool; CK(hipMalloc(&pool, pool_bytes));
   CK(hipMemset(pool, 1, pool_bytes));
   for (size_t mib : {(size_t)16, (size_t)128}) {
@@ -172,29 +174,35 @@ int main() {
     std::printf("read+write  1 MiB read, 64 KiB written    : %6.2f us\n", us);
     CK(hipFree(dst));
   }
-  // ---- gather: 8 rows x 2048 entries of K and of V out of 8 x 32768 rows (64 MiB + 64 MiB) ----
-  {
-    const int rows = 8, N = 32768, B = 2048, nsets = 4;
-    const size_t cache16 = (size_t)rows * N * 16;          // uint4 per cache (64 MiB)
-    std::vector<int32_t> h((size_t)nsets * rows * B);
+  // ---- gather: rows x B entries of K and of V out of rows x 32768 cached rows ----
+  for (int big = 0; big < 2; ++big) {
+    const int rows = big ? 32 : 8, N = 32768, B = big ? 6193 : 2048, nsets = 4;
+    const int Bp = (B + 63) / 64 * 64;                     // list padded to whole workgroups (repeats the last entry)
+    const size_t cache16 = (size_t)rows * N * 16;          // uint4 per cache (64 MiB, or 256 MiB)
+    std::vector<int32_t> h((size_t)nsets * rows * Bp);
     uint64_t s = 88172645463325252ull;
     for (int k = 0; k < nsets; ++k)
-      for (int r = 0; r < rows; ++r)
-        for (int j = 0; j < B; ++j) {
+      for (int r = 0; r < rows; ++r) {
+        std::vector<int32_t> pick(N);
+        for (int j = 0; j < N; ++j) pick[j] = j;
+        for (int j = 0; j < B; ++j) {                      // B distinct tokens, then ascending
           s ^= s << 13; s ^= s >> 7; s ^= s << 17;
-          h[((size_t)k * rows + r) * B + j] = r * N + (int)(s % N);
+          std::swap(pick[j], pick[j + (int)(s % (uint64_t)(N - j))]);
         }
+        std::sort(pick.begin(), pick.begin() + B);
+        for (int j = 0; j < Bp; ++j) h[((size_t)k * rows + r) * Bp + j] = r * N + pick[std::min(j, B - 1)];
+      }
     int32_t* idx; CK(hipMalloc(&idx, h.size() * 4));
     CK(hipMemcpy(idx, h.data(), h.size() * 4, hipMemcpyHostToDevice));
     int k = 0;
-    const double us = time_us(st, 50, [&] {
+    const double us = time_us(st, big ? 20 : 50, [&] {
       for (int i = 0; i < nsets; ++i, ++k) {
         const int set = k % nsets;
-        hipLaunchKernelGGL(gather_kernel, dim3(rows * B / 64), dim3(256), 0, st, pool + (size_t)(2 * set) * cache16,
-                           pool + (size_t)(2 * set + 1) * cache16, idx + (size_t)set * rows * B, sink);
+        hipLaunchKernelGGL(gather_kernel, dim3(rows * Bp / 64), dim3(256), 0, st, pool + (size_t)(2 * set) * cache16,
+                           pool + (size_t)(2 * set + 1) * cache16, idx + (size_t)set * rows * Bp, sink);
       }
     }) / nsets;
-    std::printf("gather      8 MiB of 256-byte rows (K+V)  : %6.2f us  (%.2f TB/s)\n", us,
+    std::printf("gather      %5.1f MiB of 256-byte rows (K+V) : %6.2f us  (%.2f TB/s)\n", (double)rows * B * 512 / 1048576.0, us,
                 (double)rows * B * 512 / us * 1e-6);
     CK(hipFree(idx));
   }

@@ -33,6 +33,10 @@ constexpr int kFuseCandLds = 1024;    // candidates resolved out of LDS; more: r
 constexpr int kFuseCountMax = 256;    // candidates ranked by counting; more: radix resolve
 // kFuseRich (fasa_internal.h): candidates per row that get a record; a record is kRecLogits floats
 // (one logit per query head of the group, log2 domain) and the candidate's V row
+#ifndef FASA_FUSE_MERGE_IN_FLIGHT
+#define FASA_FUSE_MERGE_IN_FLIGHT 32
+#endif
+constexpr int kFuseMergeInFlight = FASA_FUSE_MERGE_IN_FLIGHT;   // partials per thread in flight in the merge
 constexpr int kStashRecs = 8;          // candidates of ONE workgroup that ride along with its winners
 constexpr int kRecLogits = kMaxGroup;
 constexpr size_t kRecRowBytes = (size_t)kFuseRich * (kRecLogits * 4 + kHeadDim * 2);
@@ -341,8 +345,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     float* lsm = reinterpret_cast<float*>(big + kFuseRich * 8);                          // [kFuseRich][8]
     uint4* lvm = reinterpret_cast<uint4*>(big + kFuseRich * 8 + kFuseRich * kRecLogits * 4);   // [kFuseRich][16]
     int32_t* tk = reinterpret_cast<int32_t*>(dh);                                        // taken candidates, by rank
-    combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, nvalid, nslices, wsm, red, reinterpret_cast<float*>(big),
-                   ex_lds, [&]() {
+    auto under_loads = [&]() {
       if (t < kFuseRich) lc[t] = ce;
       reinterpret_cast<float2*>(lsm)[t] = cs;
 #pragma unroll
@@ -395,7 +398,9 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
       }
       __syncthreads();
       FASA_T(8);
-    });
+    };
+    combine_row<G, decltype(under_loads)&, kFuseMergeInFlight>(part_acc, part_ml, O, row, b, h, Hq, nvalid, nslices, wsm, red,
+                                                               reinterpret_cast<float*>(big), ex_lds, under_loads);
     FASA_T(9);
     FASA_T_PRINT(t == 0 && row == 0, "fused last(row0, slice %d): loads %llu rank(%d of %d) %llu records %llu merge %llu (x10ns)\n",
                  slice, FASA_T_D(6, 5), need, n_cand, FASA_T_D(7, 6), FASA_T_D(8, 7), FASA_T_D(9, 8));
@@ -466,7 +471,8 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   FASA_T(8);
 
   // ---- 6. merge ----
-  combine_row<G>(part_acc, part_ml, O, row, b, h, Hq, nvalid, nslices, wsm, red, reinterpret_cast<float*>(big), ex);
+  combine_row<G, NothingUnderLoads, kFuseMergeInFlight>(part_acc, part_ml, O, row, b, h, Hq, nvalid, nslices, wsm, red,
+                                                        reinterpret_cast<float*>(big), ex);
   FASA_T(9);
   FASA_T_PRINT(t == 0 && row == 0, "fused last(row0, slice %d): candload %llu resolve %llu attend(%d of %d) %llu combine %llu (x10ns)\n",
                slice, FASA_T_D(6, 5), FASA_T_D(7, 6), need, n_cand, FASA_T_D(8, 7), FASA_T_D(9, 8));

@@ -59,8 +59,7 @@ struct MfmaTile {
     for (int e = 0; e < 4; ++e) sv[e] = (c0[e] + c1[e]) * scale_log2e;
   }
   // Folds the tile into the running softmax: rows with valid[e] false get weight 0.  scs_wave: 16 floats
-  // of LDS owned by this wave (the rescale factor of head lo has to reach the lanes that hold head lo's
-  // sums, heads 4hi .. 4hi+3).
+  // of LDS owned by this wave.
   __device__ __forceinline__ void accumulate(const TileKV& kv, const float (&sv)[4], const bool (&valid)[4],
                                              float* scs_wave, int lo, int hi) {
 #pragma clang fp contract(off)
@@ -85,15 +84,24 @@ struct MfmaTile {
     const uint4 aw = make_uint4(__builtin_amdgcn_perm(ph[1], ph[0], 0x07060302u), __builtin_amdgcn_perm(ph[3], ph[2], 0x07060302u),
                                 __builtin_amdgcn_perm(pl[1], pl[0], 0x07060302u), __builtin_amdgcn_perm(pl[3], pl[2], 0x07060302u));
     const bf16x8_t pa = __builtin_bit_cast(bf16x8_t, aw);
-    if (hi == 0) scs_wave[lo] = sc;
-    // same wave writes and reads: LDS operations of a wave complete in order; the fences only keep the
-    // compiler from moving the accesses across
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const float4 s4 = *reinterpret_cast<const float4*>(scs_wave + 4 * hi);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();   // read before the next tile overwrites it
+    // The running sums only need rescaling when some head's maximum moved in this tile - after the first
+    // few tiles of a list that is rare, and the whole exchange (the factor of head lo has to reach the
+    // lanes that hold head lo's sums, through LDS) and 32 multiplies are skipped: a wave-uniform test.
+    if (__ballot(sc != 1.0f) != 0ull) {
+      if (hi == 0) scs_wave[lo] = sc;
+      // same wave writes and reads: LDS operations of a wave complete in order; the fences only keep the
+      // compiler from moving the accesses across
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const float4 s4 = *reinterpret_cast<const float4*>(scs_wave + 4 * hi);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();   // read before the next tile overwrites it
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        oc[j][0] *= s4.x; oc[j][1] *= s4.y; oc[j][2] *= s4.z; oc[j][3] *= s4.w;
+      }
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;   // which half of word j / 2
@@ -103,9 +111,7 @@ struct MfmaTile {
       const uint32_t w3 = j < 2 ? kv.vr[3].x : j < 4 ? kv.vr[3].y : j < 6 ? kv.vr[3].z : kv.vr[3].w;
       const uint32_t b01 = __builtin_amdgcn_perm(w1, w0, sel), b23 = __builtin_amdgcn_perm(w3, w2, sel);
       const bf16x8_t vb = __builtin_bit_cast(bf16x8_t, make_uint4(b01, b23, b01, b23));
-      f32x4_t o = oc[j];
-      o[0] *= s4.x; o[1] *= s4.y; o[2] *= s4.z; o[3] *= s4.w;
-      oc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vb, o, 0, 0, 0);
+      oc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vb, oc[j], 0, 0, 0);
     }
   }
   // The wave's totals to LDS: sm_m_wave, sm_l_wave [G]; sm_o_wave [G][128].  (A block barrier must follow
