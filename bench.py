@@ -42,27 +42,28 @@ LLC_BYTES = 256 << 20         # last-level (memory-side) cache the rotation has 
 # what the same counters read for a plain copy kernel of known size (see profiles/).  Keyed by
 # (workload config id, kernel name); bytes per launch.  None = not measured yet.
 MEASURED_TRAFFIC = {
-    "source_hash": "unmeasured",   # source_hash() of the kernels the counters were taken on
-    # profiles/decode_step_llama3_8b_layer_n32768_b2048_hbm_counters.txt
-    (1, "fasa_score_hist"): 16876270 + 1235328,
-    (1, "fasa_select"): 1393282 + 350168,
-    (1, "fasa_sparse_attend"): 9188383 + 1089792,
-    (1, "fasa_dense_attend"): 135503614 + 2162944,
-    # profiles/decode_step_batch16_n16384_b256_hbm_counters.txt
-    (2, "fasa_score_hist"): 134430506 + 9871694,
-    (2, "fasa_select"): 10815907 + 2746908,
-    (2, "fasa_sparse_attend"): 18315556 + 2412544,
-    (2, "fasa_dense_attend"): 1076186100 + 4558848,
-    # profiles/decode_step_longcot_batch8_gqa7_n32768_hbm_counters.txt
-    (3, "fasa_score_hist"): 67254132 + 4926245,
-    (3, "fasa_select"): 5267818 + 1915548,
-    (3, "fasa_sparse_attend"): 104514936 + 3879936,
-    (3, "fasa_dense_attend"): 539010014 + 3879936,
-    # profiles/decode_step_verylong_n131072_f32fc_b1024_hbm_counters.txt
-    (4, "fasa_score_hist"): 134342333 + 4947284,
-    (4, "fasa_select"): 4561410 + 340879,
-    (4, "fasa_sparse_attend"): 4713209 + 553216,
-    (4, "fasa_dense_attend"): 538111926 + 2162944,
+    "source_hash": "4dea75d48ba35726",   # source_hash() of the kernels the counters were taken on
+    # profiles/decode_step_tiny_1head_f32_n4096_hbm_counters.txt  (read + written)
+    (0, "fasa_dense_attend"): 4327805 + 39456,
+    (0, "fasa_score_hist"): 601110 + 21632,
+    (0, "fasa_select"): 135682 + 19846,
+    (0, "fasa_sparse_attend"): 321079 + 2976,
+    # profiles/decode_step_llama3_8b_layer_n32768_b2048_hbm_counters.txt  (read + written)
+    (1, "fasa_dense_attend"): 135500148 + 2162944,
+    (1, "fasa_score_hist"): 16890289 + 1323072,
+    (1, "fasa_select_attend"): 10530921 + 1277709,
+    # profiles/decode_step_batch16_n16384_b256_hbm_counters.txt  (read + written)
+    (2, "fasa_dense_attend"): 1076169530 + 4558848,
+    (2, "fasa_score_hist"): 134446570 + 10223479,
+    (2, "fasa_select_attend"): 27810338 + 3344361,
+    # profiles/decode_step_longcot_batch8_gqa7_n32768_hbm_counters.txt  (read + written)
+    (3, "fasa_dense_attend"): 538970767 + 3879936,
+    (3, "fasa_score_hist"): 67269290 + 5386011,
+    (3, "fasa_select_attend"): 108586153 + 5034113,
+    # profiles/decode_step_verylong_n131072_f32fc_b1024_hbm_counters.txt  (read + written)
+    (4, "fasa_dense_attend"): 538111696 + 2162944,
+    (4, "fasa_score_hist"): 134516987 + 4999569,
+    (4, "fasa_select_attend"): 9944179 + 2300815,
 }
 
 
@@ -115,7 +116,7 @@ def growing(args, w, fb, W, np, torch):
     out = {
         "metric": "us_per_decode_step", "value": round(per_step, 3), "unit": "us", "n_gpus": 1,
         "steps": steps + 1, "warmup": args.warmup, "ms_per_step": round(per_step / 1e3, 6),
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "accum_dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name + "_growing", "batch": w.batch, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "n_ctx_first": n0, "n_ctx_last": n0 + steps,
                    "budget_first": W.budget_fraction(n0), "budget_last": W.budget_fraction(n0 + steps),
@@ -182,7 +183,7 @@ def offload(args, w, fb, W, np, torch):
     out = {
         "metric": "us_per_decode_step", "value": round(us, 3), "unit": "us", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(us / 1e3, 6), "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": w.dtype, "accum_dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name + "_offload", "batch": w.batch, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "n_ctx": w.n_ctx, "budget": bsel,
                    "n_fc": w.n_fc, "storage_dtype": w.dtype, "launch": "eager", "buffer_sets": 1},
@@ -253,7 +254,7 @@ def calibrate(args, w, fb, W, np, torch):
     out = {
         "metric": "us_per_calibration_sample", "value": round(us, 3), "unit": "us", "n_gpus": 1, "steps": n_samples,
         "warmup": 1, "ms_per_step": round(us / 1e3, 6), "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": w.dtype, "accum_dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name + "_calibration", "batch": w.batch, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "n_ctx": w.n_ctx, "top_k": top_k,
                    "storage_dtype": w.dtype, "launch": "eager"},
@@ -328,7 +329,7 @@ def ragged(args, w, fb, W, np, torch):
     out = {
         "metric": "us_per_decode_step", "value": round(us, 3), "unit": "us", "n_gpus": 1, "steps": steps,
         "warmup": min(args.warmup, 8), "ms_per_step": round(us / 1e3, 6), "higher_is_better": False,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "accum_dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name + "_ragged", "batch": w.batch, "n_q_heads": w.n_q_heads,
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "n_ctx_bound": n_max,
                    "n_ctx_min": int(lens0.min()), "n_ctx_mean": round(mean_len, 1), "n_ctx_max": int(lens0.max()) + steps,
@@ -425,7 +426,7 @@ def paged(args, w, fb, W, np, torch):
     out = {
         "metric": "us_per_decode_step", "value": us, "unit": "us", "n_gpus": 1, "steps": K_steps,
         "warmup": args.warmup, "ms_per_step": round(us / 1e3, 6), "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": w.dtype, "accum_dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name + "_paged", "batch": B, "n_q_heads": w.n_q_heads, "n_kv_heads": Hkv,
                    "head_dim": D, "n_ctx": w.n_ctx, "budget": bsel, "n_fc": w.n_fc, "storage_dtype": w.dtype,
                    "page_size": page, "pool_blocks": n_pool, "block_layout": "[block][token][head][dim]",

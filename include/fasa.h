@@ -144,8 +144,14 @@ int fasa_dense_attend(const fasa_shape* shape, const void* q, const void* K, con
  *   if k_new != NULL: K[b,h,n_ctx-1,:] = k_new[b,h,:], V[b,h,n_ctx-1,:] = v_new[b,h,:]
  *                     ([batch][n_kv_heads][head_dim], dtype) and the row's dominant FCs go to Kp;
  *                     k_new and v_new must be both NULL or both non-NULL;
- *   then fasa_score -> S, fasa_topk -> T, fasa_sparse_attend -> O.
- * S and T are outputs the caller may inspect (S doubles as the score scratch). */
+ *   then S, T and O exactly as fasa_score -> S, fasa_topk -> T, fasa_sparse_attend -> O define them
+ *   (T the same set, ties towards the lower index; O up to the order of float32 additions).
+ * S and T are outputs the caller may inspect (S doubles as the score scratch).
+ * How it runs: bf16 caches take two launches - the scoring kernel, which also counts a histogram of
+ * the scores, then one kernel in which every workgroup classifies a range of tokens against the
+ * B-th score's histogram bin and attends at once over the winners it owns, the row's last workgroup
+ * settling the ties of that bin and merging the partial results.  float32 caches, rows longer than
+ * 2^20 tokens and budget >= n_ctx run the three stand-alone kernels back to back. */
 int fasa_decode_step(const fasa_shape* shape, const void* q, void* K, void* V, void* Kp,
                      const int32_t* fc_idx, const void* k_new, const void* v_new, float* S,
                      int32_t* T, float* O, void* ws, size_t ws_bytes, void* stream);
