@@ -113,8 +113,9 @@ constexpr int kFuseRich = 64;
 constexpr size_t kFuseRecBytesPerRow = (size_t)kFuseRich * (kMaxGroup * 4 + kHeadDim * 2);
 
 struct FusePlan {
-  int tpb;
-  int nslices;
+  int tpb;         // kernel instance: most tokens a workgroup can hold (0: the fused step does not apply)
+  int nslices;     // workgroups per row
+  int slice_len;   // tokens per workgroup, <= tpb, a multiple of 16
 };
 // by_sequence: lengths and budgets come from device arrays (a budget may then reach its length)
 FusePlan plan_fused(const fasa_shape& s, bool by_sequence);

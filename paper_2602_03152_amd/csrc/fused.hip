@@ -3,7 +3,7 @@
 // selected set never travels through memory on its way to the attention, one kernel boundary and the
 // serial tail of a stand-alone selection disappear, and the index set T is written on the side.
 //
-//   every workgroup (row, slice of TPB tokens):
+//   every workgroup (row, slice of at most TPB tokens):
 //     1. loads its scores, the row's adaptive histogram (kLinBins bins of lin_bin, built by the scoring
 //        kernel) and the two numbers that define the bins; finds the threshold bin: bins above it hold
 //        fewer than B tokens, bins from it upwards at least B;
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     const float* __restrict__ S, uint32_t* __restrict__ hist, RowCtl* __restrict__ ctl,
     uint2* __restrict__ cand, int32_t* __restrict__ T, float* __restrict__ O, float* __restrict__ part_acc,
-    float* __restrict__ part_ml, unsigned char* __restrict__ rec, int rows, int nslices, int Hq, int Hkv, int N_max,
+    float* __restrict__ part_ml, unsigned char* __restrict__ rec, int rows, int nslices, int slice_len, int Hq, int Hkv, int N_max,
     int n_cap, int budget_max, int t_pitch, long long sb, long long sh, long long sn, float scale_log2e,
     const int32_t* __restrict__ n_ctx_seq, const int32_t* __restrict__ budget_seq, PageMap pm) {
   constexpr int D = kHeadDim;
@@ -111,9 +111,12 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
   const int lo = lane & 15, hi = lane >> 4;
   const int N = seq_n_ctx(n_ctx_seq, b, N_max);
   const int bsel = seq_bsel(budget_seq, b, N, budget_max);
-  const int base = slice * TPB;
+  // slice_len <= TPB tokens per workgroup, a multiple of 16: the launch plan cuts a row into equal
+  // slices, so that the grid fills the machine evenly whatever the row length
+  const int base = slice * slice_len;
   if (base >= N) return;                                      // beyond this sequence (ragged batches only)
-  const int nvalid = (N + TPB - 1) / TPB;                     // workgroups of this row that take part
+  const int n_end = min(N, base + slice_len);                 // this workgroup's tokens: base .. n_end - 1
+  const int nvalid = (N + slice_len - 1) / slice_len;         // workgroups of this row that take part
   FASA_T_DECL(10);
   FASA_T(0);
 
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
     const int n = base + ((k >> 2) * 256 + t) * 4 + (k & 3);
     key[k] = score_key(v[k]);
     const uint32_t bin = lin_bin(v[k], bin_mu, bin_inv);
-    const bool ok = n < N;
+    const bool ok = n < n_end;
     win |= (ok && bin > tbin) ? (1u << k) : 0u;
     cnd |= (ok && bin == tbin) ? (1u << k) : 0u;
   }
@@ -482,20 +485,33 @@ __global__ __launch_bounds__(256) void select_attend_kernel(
 // launch
 // ---------------------------------------------------------------------------------------------
 FusePlan plan_fused(const fasa_shape& s, bool by_sequence) {
-  FusePlan p{0, 0};
+  FusePlan p{0, 0, 0};
   if (s.dtype != FASA_BF16) return p;                       // float32 caches take the staged kernels
   if (!by_sequence && s.budget >= s.n_ctx) return p;        // everything selected: nothing to select
   const long long rows = (long long)s.batch * s.n_kv_heads;
-  // Smallest slice that keeps the grid at or under two workgroups per CU (256 CUs: what is resident at
-  // once): small problems are latency-bound and gain from short slices with few winners each, large
-  // ones from fewer partials to publish and merge and fewer fixed costs per workgroup.  Measured on
-  // the five workload shapes: 1024 / 4096 / 2048 / 2048 tokens for shapes 1 - 4.
-  for (int tpb : {1024, 2048, 4096}) {
-    const int ns = (s.n_ctx + tpb - 1) / tpb;
-    if (ns > kMaxSplitsLds) continue;
-    if (rows * ns <= 2 * kAssumedCUs || tpb == 4096) { p.tpb = tpb; p.nslices = ns; return p; }
+  const long long N = s.n_ctx;
+  // The kernel runs two workgroups per CU, so a grid of up to 2 * 256 workgroups is resident at once and
+  // ends together; one workgroup more and a second, nearly empty round doubles the kernel's time.  So a
+  // row is cut into EQUAL slices, as many as keep the grid within that bound - small problems are
+  // latency-bound and gain from short slices with few winners each - but of at least 1024 tokens (shorter
+  // ones measured no gain: more partials to publish and merge) and at most 4096 (what a workgroup can
+  // hold in registers).  Rows too long for one round at 4096 tokens per slice take equal slices of at
+  // most 4096.  The kernel instance is the smallest that holds a slice.
+  const long long cap = 2LL * kAssumedCUs;
+  const long long ns_min = (N + 4095) / 4096;
+  long long ns = ns_min;
+  if (rows * ns_min <= cap) {
+    ns = cap / rows;
+    if (ns > (N + 1023) / 1024) ns = (N + 1023) / 1024;
+    if (ns > kMaxSplitsLds) ns = kMaxSplitsLds;
+    if (ns < ns_min) ns = ns_min;
   }
-  return p;                                                  // rows longer than 256 slices of 4096
+  if (ns > kMaxSplitsLds) return p;                          // rows longer than 256 slices of 4096
+  const long long len = ((N + ns - 1) / ns + 15) / 16 * 16;  // <= 4096: ns >= ns_min
+  p.slice_len = (int)len;
+  p.nslices = (int)((N + len - 1) / len);
+  p.tpb = len <= 1024 ? 1024 : (len <= 2048 ? 2048 : (len <= 3072 ? 3072 : 4096));
+  return p;
 }
 
 template <int G, int TPB>
@@ -508,7 +524,7 @@ static hipError_t launch_fused_gt(const fasa_shape& s, const FusePlan& p, const 
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)s.head_dim);
   return launch("fasa_select_attend", select_attend_kernel<G, TPB>, dim3(rows * p.nslices), dim3(256), st,
                 (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, S, hist, ctl, cand, T, O, part_acc,
-                part_ml, rec, rows, p.nslices, s.n_q_heads, s.n_kv_heads, s.n_ctx, s.n_cap, s.budget, t_pitch,
+                part_ml, rec, rows, p.nslices, p.slice_len, s.n_q_heads, s.n_kv_heads, s.n_ctx, s.n_cap, s.budget, t_pitch,
                 (long long)s.kv_stride_b, (long long)s.kv_stride_h, (long long)s.kv_stride_n, scale_log2e,
                 rl.n_ctx, rl.budget, pm);
 }
@@ -521,6 +537,7 @@ static hipError_t launch_fused_g(const fasa_shape& s, const FusePlan& p, const v
   switch (p.tpb) {
     case 1024: return launch_fused_gt<G, 1024>(s, p, q, K, V, S, hist, ctl, cand, T, O, part_acc, part_ml, rec, st, rl, pm);
     case 2048: return launch_fused_gt<G, 2048>(s, p, q, K, V, S, hist, ctl, cand, T, O, part_acc, part_ml, rec, st, rl, pm);
+    case 3072: return launch_fused_gt<G, 3072>(s, p, q, K, V, S, hist, ctl, cand, T, O, part_acc, part_ml, rec, st, rl, pm);
     case 4096: return launch_fused_gt<G, 4096>(s, p, q, K, V, S, hist, ctl, cand, T, O, part_acc, part_ml, rec, st, rl, pm);
     default: return hipErrorInvalidValue;
   }
