@@ -42,28 +42,28 @@ LLC_BYTES = 256 << 20         # last-level (memory-side) cache the rotation has 
 # what the same counters read for a plain copy kernel of known size (see profiles/).  Keyed by
 # (workload config id, kernel name); bytes per launch.  None = not measured yet.
 MEASURED_TRAFFIC = {
-    "source_hash": "4dea75d48ba35726",   # source_hash() of the kernels the counters were taken on
+    "source_hash": "6bd995ea84a2a838",   # source_hash() of the kernels the counters were taken on
     # profiles/decode_step_tiny_1head_f32_n4096_hbm_counters.txt  (read + written)
-    (0, "fasa_dense_attend"): 4327805 + 39456,
-    (0, "fasa_score_hist"): 601110 + 21632,
-    (0, "fasa_select"): 135682 + 19846,
-    (0, "fasa_sparse_attend"): 321079 + 2976,
+    (0, "fasa_dense_attend"): 4327807 + 39456,
+    (0, "fasa_score_hist"): 601144 + 21632,
+    (0, "fasa_select"): 135682 + 19851,
+    (0, "fasa_sparse_attend"): 321111 + 2976,
     # profiles/decode_step_llama3_8b_layer_n32768_b2048_hbm_counters.txt  (read + written)
-    (1, "fasa_dense_attend"): 135500148 + 2162944,
-    (1, "fasa_score_hist"): 16890289 + 1323072,
-    (1, "fasa_select_attend"): 10530921 + 1277709,
+    (1, "fasa_dense_attend"): 135500213 + 2162944,
+    (1, "fasa_score_hist"): 16890376 + 1323072,
+    (1, "fasa_select_attend"): 10539084 + 1277712,
     # profiles/decode_step_batch16_n16384_b256_hbm_counters.txt  (read + written)
-    (2, "fasa_dense_attend"): 1076169530 + 4558848,
-    (2, "fasa_score_hist"): 134446570 + 10223479,
-    (2, "fasa_select_attend"): 27810338 + 3344361,
+    (2, "fasa_dense_attend"): 1076169770 + 4558848,
+    (2, "fasa_score_hist"): 134446423 + 10223368,
+    (2, "fasa_select_attend"): 27812419 + 3344359,
     # profiles/decode_step_longcot_batch8_gqa7_n32768_hbm_counters.txt  (read + written)
-    (3, "fasa_dense_attend"): 538970767 + 3879936,
-    (3, "fasa_score_hist"): 67269290 + 5386011,
-    (3, "fasa_select_attend"): 108586153 + 5034113,
+    (3, "fasa_dense_attend"): 538972277 + 3879936,
+    (3, "fasa_score_hist"): 67269107 + 5385955,
+    (3, "fasa_select_attend"): 108590998 + 5034096,
     # profiles/decode_step_verylong_n131072_f32fc_b1024_hbm_counters.txt  (read + written)
-    (4, "fasa_dense_attend"): 538111696 + 2162944,
-    (4, "fasa_score_hist"): 134516987 + 4999569,
-    (4, "fasa_select_attend"): 9944179 + 2300815,
+    (4, "fasa_dense_attend"): 538111920 + 2162944,
+    (4, "fasa_score_hist"): 134513582 + 4998099,
+    (4, "fasa_select_attend"): 9948206 + 2300811,
 }
 
 
