@@ -366,6 +366,20 @@ def test_full_size_sampled(fb, cid, rows):
     print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
 
 
+@pytest.mark.parametrize("n_ctx,budget", [(8 * 1500 + 3, 300), (8 * 2600 + 5, 700), (8 * 3500 + 1, 1200), (8 * 4096 + 1, 500)])
+def test_equal_slices_of_every_kernel_instance(fb, n_ctx, budget):
+    """64 rows, so that the fused step cuts a row into 8 equal slices of about 1500, 2600 and 3500
+    tokens (the 2048-, 3072- and 4096-token kernel instances, none filled to its maximum, the last slice
+    ragged), and a row one token too long for 8 slices of 4096 (9 equal slices).  Two batch entries are
+    checked against the oracle."""
+    w = W.WORKLOADS[1].scaled(batch=8, n_kv_heads=8, n_q_heads=16, n_ctx=n_ctx, budget=budget)
+    x = W.make_inputs(w, n_cap=(n_ctx + 63) // 64 * 64)
+    print("equal slices: n_ctx", n_ctx, "budget", budget, flush=True)
+    d = run_step(fb, w, x)
+    n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget, rows=[0, 6])
+    print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
+
+
 def test_full_size_growing_cache(fb):
     """The long-CoT workload as the benchmark runs it: 512 consecutive steps on ONE cache at full size
     (batch 8, GQA 7, 32768 -> 33280 tokens), each appending one K/V row per (b, h) inside the scoring
