@@ -621,7 +621,8 @@ def main():
 
 
 def stage_timers(args, w, fb, W, np, torch):
-    """Three steps on one buffer set with the traced library (FASA_LIB): the kernels print their phases."""
+    """Three warm and three cold steps on one buffer set with the traced library (FASA_LIB): the kernels print
+    their phases."""
     x = W.make_inputs(w)
     dev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
     tdt = torch.int16 if w.dtype == "bf16" else torch.float32
@@ -639,7 +640,16 @@ def stage_timers(args, w, fb, W, np, torch):
     for i in range(3):
         fb.fasa_decode_step(shape, q, K, V, Kp, fc, None, None, S, T, O, ws, ws_bytes)
         torch.cuda.synchronize()
-        print("---- step %d ----" % i, flush=True)
+        print("---- step %d (warm: same buffers as the step before) ----" % i, flush=True)
+    # the same step with nothing of it left in the caches: 1 GiB is written in between (the last-level
+    # cache holds 256 MiB), as after the other layers of a model
+    junk = torch.empty((1 << 28,), dtype=torch.float32, device="cuda")
+    for i in range(3):
+        junk.fill_(float(i))
+        torch.cuda.synchronize()
+        fb.fasa_decode_step(shape, q, K, V, Kp, fc, None, None, S, T, O, ws, ws_bytes)
+        torch.cuda.synchronize()
+        print("---- step %d (cold: 1 GiB written since the step before) ----" % (3 + i), flush=True)
 
 
 def source_hash():
