@@ -641,15 +641,15 @@ def stage_timers(args, w, fb, W, np, torch):
         fb.fasa_decode_step(shape, q, K, V, Kp, fc, None, None, S, T, O, ws, ws_bytes)
         torch.cuda.synchronize()
         print("---- step %d (warm: same buffers as the step before) ----" % i, flush=True)
-    # the same step with nothing of it left in the caches: 1 GiB is written in between (the last-level
-    # cache holds 256 MiB), as after the other layers of a model
-    junk = torch.empty((1 << 28,), dtype=torch.float32, device="cuda")
+    # the same step with nothing of it left in the caches: 1 GiB is read in between (the last-level cache
+    # holds 256 MiB), which leaves the caches full of clean lines as bench.py's rotation over buffer sets does
+    junk = torch.zeros((1 << 28,), dtype=torch.float32, device="cuda")
     for i in range(3):
-        junk.fill_(float(i))
+        junk.sum().item()
         torch.cuda.synchronize()
         fb.fasa_decode_step(shape, q, K, V, Kp, fc, None, None, S, T, O, ws, ws_bytes)
         torch.cuda.synchronize()
-        print("---- step %d (cold: 1 GiB written since the step before) ----" % (3 + i), flush=True)
+        print("---- step %d (cold: 1 GiB read since the step before) ----" % (3 + i), flush=True)
 
 
 def source_hash():
