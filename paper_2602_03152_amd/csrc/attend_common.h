@@ -33,6 +33,7 @@ __device__ __forceinline__ uint4 agent_load_u128(__amdgpu_buffer_rsrc_t rs, uint
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 typedef float f32x4_ld __attribute__((ext_vector_type(4)));
+#ifndef FASA_MERGE_LOADS_TRACKED
 __device__ __forceinline__ void agent_b128_issue(f32x4_ld& dst, const void* p) {
   asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
 }
@@ -43,6 +44,17 @@ __device__ __forceinline__ void agent_b128_wait(f32x4_ld* x) {
                : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
                :: "memory");
 }
+#else
+// The fallback for a toolchain on which the build's assembly check of the form above does not hold
+// (build.py switches to it by itself): the language's own agent-scope loads, 8 bytes each, which the
+// compiler counts.  Twice the requests: the merge is 0.5 - 0.9 us slower per step.
+__device__ __forceinline__ void agent_b128_issue(f32x4_ld& dst, const void* p) {
+  const float2* p2 = reinterpret_cast<const float2*>(p);
+  const float2 a = ld_agent(p2), c = ld_agent(p2 + 1);
+  dst = f32x4_ld{a.x, a.y, c.x, c.y};
+}
+__device__ __forceinline__ void agent_b128_wait(f32x4_ld*) {}
+#endif
 
 // One more split that the merging workgroup holds in its own LDS instead of the partial buffers
 // (the fused step's threshold-bin tokens, attended by the merging workgroup itself).

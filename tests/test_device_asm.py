@@ -45,3 +45,26 @@ def test_checker_follows_the_control_flow_graph():
 @pytest.mark.parametrize("source", B.ASM_CHECKED)
 def test_untracked_loads_are_waited_for_before_any_use(tmp_path, source):
     B._check_asm(source, (), str(tmp_path), False)       # raises on a violation
+
+
+def test_build_falls_back_to_counted_loads_when_the_check_fails(monkeypatch, tmp_path):
+    """A toolchain on which the check of the hand-placed loads fails must not end in a broken library:
+    build() then compiles everything again with the compiler-counted loads.  Host logic only: the
+    compiler runs are recorded, not executed."""
+    runs, checks = [], []
+
+    def fake_check(source, extra_flags, bdir, verbose):
+        checks.append(tuple(extra_flags))
+        if B.TRACKED_FLAG not in extra_flags:
+            raise B.UntrackedLoadsTouched("%s: planted" % source)
+
+    monkeypatch.setattr(B, "_run", lambda cmd, verbose: runs.append(list(cmd)))
+    monkeypatch.setattr(B, "_check_asm", fake_check)
+    monkeypatch.setattr(B, "BUILD", str(tmp_path))
+    B.build(verbose=False)
+    assert any(B.TRACKED_FLAG not in c for c in checks) and any(B.TRACKED_FLAG in c for c in checks)
+    link = runs[-1]
+    assert "-shared" in link
+    second_round = runs[[i for i, c in enumerate(runs) if "-shared" not in c and B.TRACKED_FLAG in c][0]:]
+    compiles = [c for c in second_round if "-c" in c]
+    assert len(compiles) == len(B.SOURCES) and all(B.TRACKED_FLAG in c for c in compiles)
