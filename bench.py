@@ -42,28 +42,28 @@ LLC_BYTES = 256 << 20         # last-level (memory-side) cache the rotation has 
 # what the same counters read for a plain copy kernel of known size (see profiles/).  Keyed by
 # (workload config id, kernel name); bytes per launch.  None = not measured yet.
 MEASURED_TRAFFIC = {
-    "source_hash": "395ca5668f9415c4",   # source_hash() of the kernels the counters were taken on
+    "source_hash": "edb18815d50a8b3a",   # source_hash() of the kernels the counters were taken on
     # profiles/decode_step_tiny_1head_f32_n4096_hbm_counters.txt  (read + written)
-    (0, "fasa_dense_attend"): 4327806 + 39456,
-    (0, "fasa_score_hist"): 601128 + 21632,
-    (0, "fasa_select"): 135682 + 19852,
-    (0, "fasa_sparse_attend"): 321115 + 2976,
+    (0, "fasa_dense_attend"): 4327810 + 39456,
+    (0, "fasa_score_hist"): 601133 + 21632,
+    (0, "fasa_select"): 135682 + 19860,
+    (0, "fasa_sparse_attend"): 321111 + 2976,
     # profiles/decode_step_llama3_8b_layer_n32768_b2048_hbm_counters.txt  (read + written)
-    (1, "fasa_dense_attend"): 135500188 + 2162944,
-    (1, "fasa_score_hist"): 16890254 + 1323072,
-    (1, "fasa_select_attend"): 10539056 + 1277718,
+    (1, "fasa_dense_attend"): 135500293 + 2162944,
+    (1, "fasa_score_hist"): 16890367 + 1323072,
+    (1, "fasa_select_attend"): 10539073 + 1277719,
     # profiles/decode_step_batch16_n16384_b256_hbm_counters.txt  (read + written)
-    (2, "fasa_dense_attend"): 1076170177 + 4558848,
-    (2, "fasa_score_hist"): 134448138 + 10223560,
-    (2, "fasa_select_attend"): 27812379 + 3344360,
+    (2, "fasa_dense_attend"): 1076170460 + 4558848,
+    (2, "fasa_score_hist"): 134446381 + 10223337,
+    (2, "fasa_select_attend"): 27812435 + 3344355,
     # profiles/decode_step_longcot_batch8_gqa7_n32768_hbm_counters.txt  (read + written)
-    (3, "fasa_dense_attend"): 538971672 + 3879936,
-    (3, "fasa_score_hist"): 67269111 + 5385973,
-    (3, "fasa_select_attend"): 108589045 + 5034098,
+    (3, "fasa_dense_attend"): 538972426 + 3879936,
+    (3, "fasa_score_hist"): 67269630 + 5386022,
+    (3, "fasa_select_attend"): 108590458 + 5034110,
     # profiles/decode_step_verylong_n131072_f32fc_b1024_hbm_counters.txt  (read + written)
-    (4, "fasa_dense_attend"): 538111862 + 2162944,
-    (4, "fasa_score_hist"): 134515802 + 4999947,
-    (4, "fasa_select_attend"): 9948295 + 2300810,
+    (4, "fasa_dense_attend"): 538112279 + 2162944,
+    (4, "fasa_score_hist"): 134514100 + 4998817,
+    (4, "fasa_select_attend"): 9948239 + 2300813,
 }
 
 

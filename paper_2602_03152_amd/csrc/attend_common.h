@@ -96,7 +96,7 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
   const int t = threadIdx.x;
   const int wave = t >> 6, lane = t & 63;
   const size_t rbase = (size_t)row * stride * G;
-  FASA_T_DECL(4);
+  FASA_T_DECL(8);
   FASA_T(0);
   // (max, sum) pairs: wave w serves query heads w, w + 4; lane = split (+ 64 i).  Indices are
   // clamped, not tested: the duplicates are masked below.
@@ -130,7 +130,9 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
     }
   };
   load_round(0);
+  FASA_T(4);
   under_loads();
+  FASA_T(5);
 
 #pragma unroll
   for (int gi = 0; gi < NG; ++gi) {
@@ -169,6 +171,7 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
     // that nothing touches a destination before this point must hold however the conditions fall).
 #pragma unroll
     for (int u0 = 0; u0 < RS; u0 += 8) agent_b128_wait(&x[u0]);
+    if (k0 == 0) FASA_T(6);
 #pragma unroll
     for (int u0 = 0; u0 < RS; u0 += 8) {
       if (k0 + u0 < K) {
@@ -193,8 +196,9 @@ __device__ __forceinline__ void combine_row(const float* __restrict__ part_acc,
     k0 += RS;
   } while (k0 < K);
   FASA_T(2);
-  FASA_T_PRINT(t == 0 && row == 0, "combine: weights %llu acc %llu (x10ns) n_splits %d\n", FASA_T_D(1, 0),
-               FASA_T_D(2, 1), n_splits);
+  FASA_T_PRINT(t == 0 && row == 0,
+               "combine: requests %llu under-loads work %llu weights %llu partials arrive %llu sum %llu (x10ns) n_splits %d\n",
+               FASA_T_D(4, 0), FASA_T_D(5, 4), FASA_T_D(1, 5), FASA_T_D(6, 1), FASA_T_D(2, 6), n_splits);
   if constexpr (P > 1) {
     float4* xb = reinterpret_cast<float4*>(xbuf);
     if (owner && part > 0) xb[(part - 1) * C + c0] = a;
