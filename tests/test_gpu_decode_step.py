@@ -189,6 +189,35 @@ def test_decode_step_random_shapes(fb, case):
     print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
 
 
+def _random_large_shapes(n_cases, seed=4242):
+    """Seeded draw over what the fused step's launch plan branches on at sizes beyond the small cases:
+    row count 1 .. 128, row length up to 45000 (equal slices of every length, every kernel instance, one
+    and several resident rounds), budget from 1 % to half of the row, every GQA group size."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n_cases):
+        hkv = int(rng.choice([1, 2, 4, 8]))
+        batch = int(rng.choice([1, 2, 4, 8, 16]))
+        G = int(rng.integers(1, 9))
+        n_ctx = int(rng.integers(1000, min(45000, 1_400_000 // (hkv * batch))))
+        budget = int(max(1, rng.choice([0.01, 0.05, 0.189, 0.5]) * n_ctx))
+        out.append(dict(batch=batch, n_kv_heads=hkv, n_q_heads=hkv * G, n_ctx=n_ctx, budget=budget,
+                        n_fc=int(rng.choice([16, 32, 8]))))
+    return out
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_decode_step_random_large_shapes(fb, case):
+    kw = _random_large_shapes(12)[case]
+    w = W.WORKLOADS[1].scaled(**kw)
+    x = W.make_inputs(w, n_cap=(w.n_ctx + 63) // 64 * 64)
+    print("large random shape", case, kw, flush=True)
+    d = run_step(fb, w, x)
+    n_diff, o_err = compare_step(w, x["q"], x["K"], x["V"], x["fc_idx"], d, w.n_ctx, w.budget,
+                                 rows=sorted({0, w.batch - 1}))
+    print("  set diff vs oracle:", n_diff, " max |O err|:", o_err, flush=True)
+
+
 def test_all_fcs_full_budget_is_dense_attention(fb):
     """F = d/2 and B = N on the device: the fused step equals the oracle's dense attention and the
     device's own dense kernel."""
